@@ -1,0 +1,10 @@
+"""fp64 CPU oracle for the YOCO attention hot path.
+
+TEST INFRASTRUCTURE ONLY. Nothing in the product package may import this
+package; only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg
+use it. It shares no code with the HIP path.
+"""
+from .yoco_oracle import (  # noqa: F401
+    swa_row, swa, rmsnorm, global_kv, cross_attn_row, cross_attn,
+    swiglu, yoco_stack, kv_cache_bytes_per_token,
+)

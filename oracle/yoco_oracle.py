@@ -1,0 +1,160 @@
+"""Plain fp64 definitions of what the YOCO attention hot path computes.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring). Every function is the
+definition from the paper written out with numpy in float64: no tiling, no
+online softmax, no split-KV, no fusion. A matrix product may serve as a step.
+Positions are 0-based here; the paper counts from 1.
+
+Pins (tests/test_oracle_pins.py): brute-force dense masked softmax on tiny
+inputs, torch's CPU scaled_dot_product_attention / rms_norm / silu as library
+routines, closed forms (equal keys -> running mean, window 1 -> V, constant V),
+locality and causality under perturbation, GQA replication, the early-exit and
+prefix invariants of the stack, and the paper's cache-size arithmetic
+(section 4.4, the KV-cache-per-token figure: 128K tokens per GB at 65B).
+No function here is "parity unpinned".
+
+Readings of points the paper leaves open (all listed in the design doc):
+  * `scale` is an explicit argument; Eq. 8 prints no 1/sqrt(d), Eq. 3 defers
+    to "standard multi-head attention". The configurations use 1/sqrt(d).
+  * Eq. 8's mask  i - C < j <= i  means a row sees itself and the C-1 keys
+    before it: min(i+1, C) keys.
+  * GQA: query head h reads KV head h // (Hq // Hkv).
+  * LN is RMSNorm with its own gain vector and eps = 1e-6, no bias.
+"""
+import numpy as np
+
+F64 = np.float64
+
+
+def _softmax_weighted_sum(q, Kj, Vj, scale):
+    """softmax_j(scale * q.k_j) applied to the rows v_j (one query, one head).
+
+    q [d], Kj [n,d], Vj [n,d] -> [d]. The max is subtracted before exp, which
+    leaves the softmax unchanged and avoids overflow.
+    """
+    s = scale * (Kj @ q)
+    p = np.exp(s - s.max())
+    p = p / p.sum()
+    return p @ Vj
+
+
+def swa_row(Q, K, V, i, h, window, scale):
+    """Row i, head h of sliding-window attention (section 3.2, Eq. 8).
+
+    B_ij = 0 iff i - C < j <= i, so the visible keys are j in
+    [max(0, i-C+1), i]. Q [T,Hq,d]; K, V [T,Hkv,d]; returns [d] float64.
+    """
+    Hq, Hkv = Q.shape[1], K.shape[1]
+    g = h // (Hq // Hkv)
+    j0 = max(0, i - window + 1)
+    q = np.asarray(Q[i, h], dtype=F64)
+    Kj = np.asarray(K[j0:i + 1, g], dtype=F64)
+    Vj = np.asarray(V[j0:i + 1, g], dtype=F64)
+    return _softmax_weighted_sum(q, Kj, Vj, scale)
+
+
+def swa(Q, K, V, window, scale):
+    """head_h = softmax(Q_h K_h^T + B) V_h for every row and head (Eq. 8),
+    before the output projection W_O. Returns [T,Hq,d] float64."""
+    T, Hq, _ = Q.shape
+    O = np.empty((T, Hq, V.shape[2]), dtype=F64)
+    for h in range(Hq):
+        for i in range(T):
+            O[i, h] = swa_row(Q, K, V, i, h, window, scale)
+    return O
+
+
+def rmsnorm(X, gain, eps=1e-6):
+    """RMSNorm, the paper's LN (section 2.1): x / sqrt(mean(x^2) + eps) * gain."""
+    X = np.asarray(X, dtype=F64)
+    ms = (X * X).mean(axis=-1, keepdims=True)
+    return X / np.sqrt(ms + eps) * np.asarray(gain, dtype=F64)
+
+
+def global_kv(X, gain, W_K, W_V, Hkv, eps=1e-6):
+    """Global KV cache of the cross-decoder (section 2.2, Eq. 2):
+    K^ = LN(X^{L/2}) W_K,  V^ = LN(X^{L/2}) W_V, reshaped to [T,Hkv,d]."""
+    Xn = rmsnorm(X, gain, eps)
+    Kh = Xn @ np.asarray(W_K, dtype=F64)
+    Vh = Xn @ np.asarray(W_V, dtype=F64)
+    T = X.shape[0]
+    return Kh.reshape(T, Hkv, -1), Vh.reshape(T, Hkv, -1)
+
+
+def cross_attn_row(Q, Khat, Vhat, i, h, q_pos0, scale):
+    """Row i, head h of the cross-decoder's attention (section 2.2, Eq. 3):
+    standard causal attention of the query at absolute position q_pos0 + i
+    over cache rows j <= q_pos0 + i, with grouped-query heads."""
+    Hq, Hkv = Q.shape[1], Khat.shape[1]
+    g = h // (Hq // Hkv)
+    p = q_pos0 + i
+    q = np.asarray(Q[i, h], dtype=F64)
+    Kj = np.asarray(Khat[:p + 1, g], dtype=F64)
+    Vj = np.asarray(Vhat[:p + 1, g], dtype=F64)
+    return _softmax_weighted_sum(q, Kj, Vj, scale)
+
+
+def cross_attn(Q, Khat, Vhat, q_pos0, scale):
+    """Attention(Q^, K^, V^) of Eq. 3 for Tq query rows; decode is Tq = 1 with
+    q_pos0 = len - 1 (the new token's own row is already in the cache: Eq. 2
+    comes before Eq. 3 and the mask is j <= i). Returns [Tq,Hq,d] float64."""
+    Tq, Hq, _ = Q.shape
+    O = np.empty((Tq, Hq, Vhat.shape[2]), dtype=F64)
+    for h in range(Hq):
+        for i in range(Tq):
+            O[i, h] = cross_attn_row(Q, Khat, Vhat, i, h, q_pos0, scale)
+    return O
+
+
+def swiglu(X, W_G, W_1, W_2):
+    """SwiGLU(X) = (swish(X W_G) * X W_1) W_2 with swish(x) = x * sigmoid(x)
+    (section 2.1)."""
+    X = np.asarray(X, dtype=F64)
+    a = X @ np.asarray(W_G, dtype=F64)
+    b = X @ np.asarray(W_1, dtype=F64)
+    return ((a / (1.0 + np.exp(-a))) * b) @ np.asarray(W_2, dtype=F64)
+
+
+def yoco_stack(tokens, w, mode="full"):
+    """Decoder-decoder stack (section 2, Eq. 1-3, Fig. 2) -> logits.
+
+    w: dict with 'embed' [vocab,dm]; 'self' = list of layers with keys
+    ln1, W_Q, W_K, W_V, W_O, ln2, W_G, W_1, W_2; 'kv' = {ln, W_K, W_V};
+    'cross' = list of layers with keys ln1, W_Q, W_O, ln2, W_G, W_1, W_2;
+    'final_ln', 'W_out'; ints 'Hq', 'Hkv_self', 'Hkv', 'd', 'window'; 'eps'.
+    mode 'full': every row goes through the cross-decoder -> logits [T,vocab].
+    mode 'early_exit' (Fig. 3, section 2.3): the self-decoder and Eq. 2 run on
+    all rows, only the last row enters the cross-decoder -> logits [1,vocab].
+    """
+    Hq, d, eps = w["Hq"], w["d"], w["eps"]
+    scale = 1.0 / np.sqrt(d)
+    X = np.asarray(w["embed"], dtype=F64)[np.asarray(tokens)]
+    T = X.shape[0]
+    for L in w["self"]:                                   # Eq. 1
+        Xn = rmsnorm(X, L["ln1"], eps)
+        Q = (Xn @ np.asarray(L["W_Q"], F64)).reshape(T, Hq, d)
+        K = (Xn @ np.asarray(L["W_K"], F64)).reshape(T, w["Hkv_self"], d)
+        V = (Xn @ np.asarray(L["W_V"], F64)).reshape(T, w["Hkv_self"], d)
+        A = swa(Q, K, V, w["window"], scale).reshape(T, Hq * d)
+        Y = A @ np.asarray(L["W_O"], F64) + X
+        X = swiglu(rmsnorm(Y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + Y
+    Khat, Vhat = global_kv(X, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)  # Eq. 2
+    if mode == "early_exit":
+        X, q_pos0 = X[T - 1:T], T - 1
+    elif mode == "full":
+        q_pos0 = 0
+    else:
+        raise ValueError(mode)
+    Tq = X.shape[0]
+    for L in w["cross"]:                                  # Eq. 3
+        Qh = (rmsnorm(X, L["ln1"], eps) @ np.asarray(L["W_Q"], F64)).reshape(Tq, Hq, d)
+        A = cross_attn(Qh, Khat, Vhat, q_pos0, scale).reshape(Tq, Hq * d)
+        Y = A @ np.asarray(L["W_O"], F64) + X
+        X = swiglu(rmsnorm(Y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + Y
+    return rmsnorm(X, w["final_ln"], eps) @ np.asarray(w["W_out"], F64)
+
+
+def kv_cache_bytes_per_token(Hkv, d, elem_bytes, cached_layers=1):
+    """Bytes of K plus V kept per token. YOCO keeps one global pair whatever the
+    depth (cached_layers = 1, Table 1); a Transformer keeps one per layer."""
+    return 2 * Hkv * d * elem_bytes * cached_layers

@@ -1,0 +1,296 @@
+"""Pins of the fp64 oracle to things other than itself (CPU only).
+
+The paper prints no worked numeric example of attention, so the oracle is
+pinned by: a dense brute force that materialises the literal mask matrix B of
+Eq. 8, torch's CPU library routines (scaled_dot_product_attention, rms_norm,
+silu), closed forms, locality/causality invariants, the GQA replication
+invariant, the early-exit and prefix invariants of the stack (Fig. 3), and the
+cache-size numbers the paper does print (tests/golden/kv_cache_tokens_per_gb.txt).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+import yoco_synth as ys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def rand_qkv(seed, T, Hq, Hkv, d):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, Hq, d)), rng.standard_normal((T, Hkv, d)),
+            rng.standard_normal((T, Hkv, d)))
+
+
+def brute_force(Q, K, V, mask_fn, scale):
+    """Dense T x N scores, the literal additive mask matrix with -inf, row
+    softmax, product. Written independently of the oracle (element loops for
+    the mask, no max subtraction: tiny inputs only)."""
+    Tq, Hq, d = Q.shape
+    N, Hkv, _ = K.shape
+    G = Hq // Hkv
+    O = np.zeros((Tq, Hq, d))
+    for h in range(Hq):
+        S = np.zeros((Tq, N))
+        for i in range(Tq):
+            for j in range(N):
+                S[i, j] = scale * sum(Q[i, h, e] * K[j, h // G, e] for e in range(d))
+                S[i, j] += 0.0 if mask_fn(i, j) else -np.inf
+        E = np.exp(S)
+        P = E / E.sum(axis=1, keepdims=True)
+        for i in range(Tq):
+            for e in range(d):
+                O[i, h, e] = sum(P[i, j] * V[j, h // G, e] for j in range(N))
+    return O
+
+
+# ------------------------------------------------------------------ SWA (Eq. 8)
+@pytest.mark.parametrize("T,C", [(16, 4), (13, 1), (12, 12), (9, 50), (16, 5)])
+def test_swa_matches_brute_force_with_literal_mask(T, C):
+    Q, K, V = rand_qkv(1, T, 2, 2, 8)
+    ref = brute_force(Q, K, V, lambda i, j: i - C < j <= i, 0.37)
+    assert np.abs(oracle.swa(Q, K, V, C, 0.37) - ref).max() < 1e-12
+
+
+def test_swa_gqa_matches_brute_force():
+    Q, K, V = rand_qkv(2, 10, 6, 2, 4)
+    ref = brute_force(Q, K, V, lambda i, j: i - 3 < j <= i, 0.5)
+    assert np.abs(oracle.swa(Q, K, V, 3, 0.5) - ref).max() < 1e-12
+
+
+def sdpa(Q, K, V, mask, scale):
+    """torch CPU library attention in float64; Q [Tq,Hq,d], K/V [N,Hkv,d]."""
+    G = Q.shape[1] // K.shape[1]
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    k = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    v = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    o = F.scaled_dot_product_attention(q, k, v, attn_mask=torch.from_numpy(mask), scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def test_swa_matches_library_attention_with_band_mask():
+    T, C, d = 96, 17, 16
+    Q, K, V = rand_qkv(3, T, 4, 2, d)
+    i, j = np.arange(T)[:, None], np.arange(T)[None, :]
+    band = (j <= i) & (j > i - C)
+    ref = sdpa(Q, K, V, band, 1 / np.sqrt(d))
+    assert np.abs(oracle.swa(Q, K, V, C, 1 / np.sqrt(d)) - ref).max() < 1e-12
+
+
+@pytest.mark.parametrize("C", [64, 65, 1000])
+def test_swa_window_at_least_T_is_full_causal_attention(C):
+    T, d = 64, 8
+    Q, K, V = rand_qkv(4, T, 2, 2, d)
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    k = torch.from_numpy(K).permute(1, 0, 2)[None]
+    v = torch.from_numpy(V).permute(1, 0, 2)[None]
+    ref = F.scaled_dot_product_attention(q, k, v, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.abs(oracle.swa(Q, K, V, C, 1 / np.sqrt(d)) - ref).max() < 1e-12
+
+
+def test_swa_window_one_returns_v():
+    Q, K, V = rand_qkv(5, 20, 3, 3, 8)
+    assert np.array_equal(oracle.swa(Q, K, V, 1, 0.3), V)
+
+
+def test_swa_equal_keys_gives_running_mean_of_v():
+    T, C = 40, 7
+    Q, K, V = rand_qkv(6, T, 2, 1, 8)
+    K[:] = K[0]
+    O = oracle.swa(Q, K, V, C, 0.9)
+    for i in range(T):
+        mean = V[max(0, i - C + 1):i + 1, 0].mean(axis=0)
+        assert np.abs(O[i] - mean).max() < 1e-13
+
+
+def test_swa_constant_v_and_key_count():
+    T, C = 30, 6
+    Q, K, V = rand_qkv(7, T, 2, 2, 4)
+    V[:] = 1.0        # output = sum of the row's probabilities = 1
+    assert np.abs(oracle.swa(Q, K, V, C, 1.0) - 1.0).max() < 1e-14
+    # one-hot V columns expose the weights: row i has exactly min(i+1, C) non-zeros
+    Vh = np.zeros((T, 1, T))
+    Vh[np.arange(T), 0, np.arange(T)] = 1.0
+    W = oracle.swa(Q[:, :1], K[:, :1], Vh, C, 1.0)[:, 0]     # [T, T] = the probabilities
+    for i in range(T):
+        nz = np.nonzero(W[i])[0]
+        assert len(nz) == min(i + 1, C) and nz.min() == max(0, i - C + 1) and nz.max() == i
+    assert np.abs(W.sum(axis=1) - 1).max() < 1e-14
+
+
+def test_swa_locality():
+    T, C, j = 50, 8, 20
+    Q, K, V = rand_qkv(8, T, 2, 2, 4)
+    O0 = oracle.swa(Q, K, V, C, 0.5)
+    K2, V2 = K.copy(), V.copy()
+    K2[j] += 1.0
+    V2[j] -= 2.0
+    changed = np.nonzero(np.abs(oracle.swa(Q, K2, V2, C, 0.5) - O0).max(axis=(1, 2)) > 0)[0]
+    assert changed.tolist() == list(range(j, j + C))
+
+
+def test_swa_scale_matters_and_sign():
+    # a transposed operand, dropped scale or flipped sign would fail here:
+    # two keys, scores s*q.k; closed form of a 2-way softmax
+    Q = np.array([[[0.0, 0.0]], [[1.0, 2.0]]])
+    K = np.array([[[3.0, -1.0]], [[0.5, 0.25]]])
+    V = np.array([[[1.0, 0.0]], [[0.0, 1.0]]])
+    s0, s1 = 0.7 * (3.0 - 2.0), 0.7 * (0.5 + 0.5)
+    p0 = np.exp(s0) / (np.exp(s0) + np.exp(s1))
+    O = oracle.swa(Q, K, V, 2, 0.7)
+    assert np.allclose(O[1, 0], [p0, 1 - p0], atol=1e-15)
+    assert np.array_equal(O[0, 0], [1.0, 0.0])
+
+
+# -------------------------------------------------------- cross-attention (Eq. 3)
+@pytest.mark.parametrize("q_pos0,Tq,N", [(0, 12, 12), (5, 4, 12), (11, 1, 12)])
+def test_cross_attn_matches_brute_force(q_pos0, Tq, N):
+    rng = np.random.default_rng(9)
+    Q = rng.standard_normal((Tq, 4, 8))
+    K, V = rng.standard_normal((N, 2, 8)), rng.standard_normal((N, 2, 8))
+    ref = brute_force(Q, K, V, lambda i, j: j <= q_pos0 + i, 0.41)
+    assert np.abs(oracle.cross_attn(Q, K, V, q_pos0, 0.41) - ref).max() < 1e-12
+
+
+def test_cross_attn_same_tokens_is_causal_self_attention_and_wide_swa():
+    T, d = 48, 16
+    Q, K, V = rand_qkv(10, T, 6, 2, d)
+    i, j = np.arange(T)[:, None], np.arange(T)[None, :]
+    ref = sdpa(Q, K, V, j <= i, 1 / np.sqrt(d))
+    got = oracle.cross_attn(Q, K, V, 0, 1 / np.sqrt(d))
+    assert np.abs(got - ref).max() < 1e-12
+    assert np.abs(got - oracle.swa(Q, K, V, T, 1 / np.sqrt(d))).max() < 1e-13
+
+
+def test_cross_attn_decode_is_last_row_and_causal():
+    T, d = 33, 8
+    Q, K, V = rand_qkv(11, T, 4, 1, d)
+    full = oracle.cross_attn(Q, K, V, 0, 0.3)
+    dec = oracle.cross_attn(Q[T - 1:], K, V, T - 1, 0.3)
+    assert np.abs(dec[0] - full[T - 1]).max() < 1e-14
+    K2 = K.copy()
+    K2[20] += 3.0
+    changed = np.nonzero(np.abs(oracle.cross_attn(Q, K2, V, 0, 0.3) - full).max(axis=(1, 2)) > 0)[0]
+    assert changed.min() == 20 and len(changed) == T - 20
+
+
+def test_gqa_replication_invariant():
+    T, d, G = 24, 8, 3
+    Q, K, V = rand_qkv(12, T, 6, 2, d)
+    Kr, Vr = np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)
+    assert np.array_equal(oracle.swa(Q, K, V, 5, 0.4), oracle.swa(Q, Kr, Vr, 5, 0.4))
+    assert np.array_equal(oracle.cross_attn(Q, K, V, 0, 0.4), oracle.cross_attn(Q, Kr, Vr, 0, 0.4))
+
+
+# ---------------------------------------------------- RMSNorm, Eq. 2, SwiGLU
+def test_rmsnorm_and_global_kv_against_library():
+    rng = np.random.default_rng(13)
+    X, g = rng.standard_normal((7, 32)), rng.standard_normal(32)
+    ref = F.rms_norm(torch.from_numpy(X), (32,), torch.from_numpy(g), eps=1e-6).numpy()
+    assert np.abs(oracle.rmsnorm(X, g, 1e-6) - ref).max() < 1e-14
+    # closed form: a constant row c maps to gain * c / sqrt(c^2 + eps)
+    c = np.full((1, 32), -3.0)
+    assert np.allclose(oracle.rmsnorm(c, g, 1e-6), g * -3.0 / np.sqrt(9 + 1e-6), atol=1e-15)
+    WK, WV = rng.standard_normal((32, 16)), rng.standard_normal((32, 16))
+    Kh, Vh = oracle.global_kv(X, g, WK, WV, Hkv=2)
+    assert Kh.shape == (7, 2, 8)
+    assert np.abs(Kh.reshape(7, 16) - ref @ WK).max() < 1e-13
+    assert np.abs(Vh.reshape(7, 16) - ref @ WV).max() < 1e-13
+    # W_K = I picks the normalised rows themselves; head h holds columns [h*d, (h+1)*d)
+    Ki, _ = oracle.global_kv(X, g, np.eye(32), np.eye(32), Hkv=4)
+    assert np.abs(Ki[:, 1, :] - ref[:, 8:16]).max() < 1e-14
+
+
+def test_swiglu_against_library():
+    rng = np.random.default_rng(14)
+    X = rng.standard_normal((5, 16))
+    WG, W1, W2 = rng.standard_normal((16, 24)), rng.standard_normal((16, 24)), rng.standard_normal((24, 16))
+    t = torch.from_numpy
+    ref = ((F.silu(t(X) @ t(WG)) * (t(X) @ t(W1))) @ t(W2)).numpy()
+    assert np.abs(oracle.swiglu(X, WG, W1, W2) - ref).max() < 1e-13
+
+
+# --------------------------------------------------------- the stack (Fig. 2, 3)
+SMALL = dict(d_model=32, Hq=4, Hkv_self=2, Hkv=1, d=8, n_self=2, n_cross=2, window=6, ffn=48, vocab=50, eps=1e-6)
+
+
+def test_early_exit_equals_full_forward_last_row():
+    w = ys.stack_weights(0, SMALL, "f32")
+    for k in ("self", "cross"):          # larger weights so attention is not near-uniform
+        for L in w[k]:
+            for n in ("W_Q", "W_K", "W_V"):
+                if n in L:
+                    L[n] = L[n] * 30
+    tok = ys.tokens(0, 40, 50)
+    full = oracle.yoco_stack(tok, w, "full")
+    ee = oracle.yoco_stack(tok, w, "early_exit")
+    assert full.shape == (40, 50) and ee.shape == (1, 50)
+    assert np.abs(ee[0] - full[-1]).max() < 1e-12
+
+
+def test_prefix_invariance_decoder_only_behaviour():
+    w = ys.stack_weights(1, SMALL, "f32")
+    tok = ys.tokens(1, 30, 50)
+    full = oracle.yoco_stack(tok, w, "full")
+    for t in (0, 5, 6, 17):
+        short = oracle.yoco_stack(tok[:t + 1], w, "early_exit")
+        assert np.abs(short[0] - full[t]).max() < 1e-12
+
+
+def test_stack_matches_library_composition():
+    """The same stack assembled from torch library ops (rms_norm, sdpa with
+    masks, silu) in float64."""
+    w = ys.stack_weights(2, SMALL, "f32")
+    tok = ys.tokens(2, 25, 50)
+    T, Hq, d, eps = 25, SMALL["Hq"], SMALL["d"], 1e-6
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    rn = lambda x, g: F.rms_norm(x, (x.shape[-1],), t(g), eps=eps)
+    ffn = lambda x, L: (F.silu(x @ t(L["W_G"])) * (x @ t(L["W_1"]))) @ t(L["W_2"])
+    i, j = np.arange(T)[:, None], np.arange(T)[None, :]
+    band, causal = (j <= i) & (j > i - SMALL["window"]), j <= i
+    X = t(w["embed"])[torch.from_numpy(tok)]
+    for L in w["self"]:
+        xn = rn(X, L["ln1"])
+        A = sdpa((xn @ t(L["W_Q"])).reshape(T, Hq, d).numpy(), (xn @ t(L["W_K"])).reshape(T, 2, d).numpy(),
+                 (xn @ t(L["W_V"])).reshape(T, 2, d).numpy(), band, 1 / np.sqrt(d))
+        Y = t(A).reshape(T, Hq * d) @ t(L["W_O"]) + X
+        X = ffn(rn(Y, L["ln2"]), L) + Y
+    xn = rn(X, w["kv"]["ln"])
+    Kh, Vh = (xn @ t(w["kv"]["W_K"])).reshape(T, 1, d).numpy(), (xn @ t(w["kv"]["W_V"])).reshape(T, 1, d).numpy()
+    for L in w["cross"]:
+        A = sdpa((rn(X, L["ln1"]) @ t(L["W_Q"])).reshape(T, Hq, d).numpy(), Kh, Vh, causal, 1 / np.sqrt(d))
+        Y = t(A).reshape(T, Hq * d) @ t(L["W_O"]) + X
+        X = ffn(rn(Y, L["ln2"]), L) + Y
+    ref = (rn(X, w["final_ln"]) @ t(w["W_out"])).numpy()
+    assert np.abs(oracle.yoco_stack(tok, w, "full") - ref).max() < 1e-12
+
+
+# ------------------------------------------------ the paper's printed cache numbers
+def test_cache_arithmetic_matches_paper_numbers():
+    vals = {}
+    with open(os.path.join(HERE, "golden", "kv_cache_tokens_per_gb.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    per_tok = oracle.kv_cache_bytes_per_token(int(vals["kv_heads"]), int(vals["head_dim"]), int(vals["elem_bytes"]))
+    per_tok_tf = oracle.kv_cache_bytes_per_token(int(vals["kv_heads"]), int(vals["head_dim"]),
+                                                 int(vals["elem_bytes"]), cached_layers=int(vals["layers"]))
+    assert 2 ** 30 // per_tok == vals["yoco_tokens_per_gib"]
+    assert round(2 ** 30 / per_tok_tf / 1000, 1) == vals["transformer_tokens_per_gib_rounded_to_0.1k"]
+    assert per_tok_tf / per_tok == vals["reduction_factor"]
+
+
+# ---------------------------------------------------------------- input module
+def test_bf16_rounding_is_rne_and_idempotent():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.1415927, 1e-30, 65504.0], dtype=np.float32)
+    r = ys.round_to(x, "bf16")
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(r, ref)
+    assert np.array_equal(ys.round_to(r, "bf16"), r)
+    big = np.random.default_rng(0).standard_normal(100000).astype(np.float32)
+    assert np.array_equal(ys.round_to(big, "bf16"), torch.from_numpy(big).to(torch.bfloat16).float().numpy())
