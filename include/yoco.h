@@ -1,0 +1,140 @@
+/*
+ * libyoco -- the attention hot path of YOCO ("You Only Cache Once",
+ * arXiv 2405.05254) for AMD MI355X (gfx950).
+ *
+ * Four operations, each a hand-written HIP kernel behind a plain C ABI:
+ *   yoco_swa_prefill          sliding-window attention of the self-decoder
+ *                             (section 3.2, Eq. 8)
+ *   yoco_global_kv_write      store rows of the once-only global K^/V^ cache
+ *                             (section 2.2, Eq. 2; the projection is the caller's)
+ *   yoco_cross_attn_prefill   causal GQA attention of Tq query rows over the
+ *                             global cache (section 2.2, Eq. 3)
+ *   yoco_cross_attn_decode    the same for one new token per sequence, split
+ *                             over the cache and merged by log-sum-exp
+ *
+ * Conventions
+ *   - Every pointer named q/k/v/o/lens/workspace/mem is DEVICE memory owned by
+ *     the caller. The library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns (the cache descriptor is a plain struct the
+ *     caller holds). Pointers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise.
+ *   - Tensors are dense and row-major; the last index is contiguous.
+ *     [T,H,d] means element (t,h,e) at offset ((t*H)+h)*d + e.
+ *   - Positions are 0-based. `scale` multiplies q.k before the softmax (the
+ *     paper's Eq. 8 prints none; Eq. 3 defers to standard attention, whose
+ *     value is 1/sqrt(d)).
+ *   - GQA: query head h reads KV head h / (Hq / Hkv); Hq must be a multiple of
+ *     Hkv.
+ *   - Every call validates its arguments before launching anything and
+ *     returns YOCO_OK (0) or a negative yoco_status; a failing call has no
+ *     side effect. yoco_last_error_string() describes the last failure on the
+ *     calling thread.
+ *   - Arithmetic: products of the stored dtype, fp32 accumulation and fp32
+ *     softmax; outputs are rounded once (to nearest even) to the dtype.
+ */
+#ifndef YOCO_H
+#define YOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum yoco_status {
+  YOCO_OK = 0,
+  YOCO_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, out-of-range position */
+  YOCO_ERR_UNSUPPORTED = -2, /* dtype / head_dim / group size with no kernel */
+  YOCO_ERR_ALIGNMENT = -3,   /* pointer not 16-byte aligned or d not a multiple of 8 */
+  YOCO_ERR_WORKSPACE = -4,   /* workspace or cache memory too small */
+  YOCO_ERR_HIP = -5          /* the HIP runtime refused a launch */
+} yoco_status;
+
+typedef enum yoco_dtype { YOCO_F32 = 0, YOCO_BF16 = 1 } yoco_dtype;
+
+/*
+ * Descriptor of the global KV cache (section 2.2: one K^/V^ pair per sequence,
+ * shared by all cross-decoder layers; Table 1: O((N+L)D) memory).
+ * Layout in the caller's memory block: a K plane followed by a V plane, each
+ * [B][Hkv][N_cap][d] -- head-major, so the rows one KV head streams during
+ * decode are contiguous (d * sizeof(dtype) bytes each, 256 B at d=128 bf16).
+ * Bytes per cached token = 2 * Hkv * d * sizeof(dtype), whatever the depth.
+ */
+typedef struct yoco_kv_cache {
+  void* k;          /* device: K plane */
+  void* v;          /* device: V plane */
+  int32_t B;        /* sequences */
+  int32_t Hkv;      /* KV heads */
+  int32_t d;        /* head dimension */
+  int32_t dtype;    /* yoco_dtype */
+  int64_t N_cap;    /* rows per sequence the planes can hold */
+} yoco_kv_cache;
+
+/* Bytes the cache needs: 2 * B * Hkv * N_cap * d * sizeof(dtype). Host only. */
+int yoco_kv_cache_bytes(int B, int Hkv, int d, int64_t N_cap, int dtype, size_t* bytes);
+
+/* Fill `out` for a caller-allocated block `mem` of `bytes` bytes (device
+ * memory, 256-byte aligned). Host only; the memory is not touched. */
+int yoco_kv_cache_init(void* mem, size_t bytes, int B, int Hkv, int d, int64_t N_cap, int dtype,
+                       yoco_kv_cache* out);
+
+/*
+ * Sliding-window attention, Eq. 8 without the W_O product:
+ *   o[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:] . k[b,j,g,:]) v[b,j,g,:],
+ *   j in [max(0, i-window+1), i],  g = h / (Hq/Hkv)
+ * (the mask  i - C < j <= i : a row sees itself and the window-1 keys before).
+ * q, o: [B,T,Hq,d]; k, v: [B,T,Hkv,d]; all of `dtype`. window >= 1; a window
+ * >= T is plain causal attention.
+ */
+int yoco_swa_prefill(const void* q, const void* k, const void* v, void* o, int B, int64_t T, int Hq,
+                     int Hkv, int d, int64_t window, float scale, int dtype, void* stream);
+
+/*
+ * Store n projected rows K^[pos0..pos0+n), V^[pos0..pos0+n) of sequence b into
+ * the cache (Eq. 2 is computed by the caller: RMSNorm and the two GEMMs).
+ * k, v: [n,Hkv,d] of `src_dtype`; rows are converted to the cache dtype
+ * (round to nearest even). Requires 0 <= pos0, pos0 + n <= N_cap, 0 <= b < B.
+ * n == 0 is a no-op.
+ */
+int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, int b, int64_t pos0,
+                         int64_t n, int src_dtype, void* stream);
+
+/*
+ * Cross-decoder attention of Eq. 3 for Tq query rows of sequence b; row i has
+ * absolute position q_pos0 + i and attends to cache rows j <= q_pos0 + i
+ * (causal). q, o: [Tq,Hq,d] of the cache dtype. Requires q_pos0 + Tq <= N_cap;
+ * the rows read must have been written.
+ */
+int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0,
+                            int64_t Tq, int Hq, float scale, void* stream);
+
+/* Workspace for yoco_cross_attn_decode on this cache with Hq query heads:
+ * `splits` partial results (running max, sum, d-vector in fp32) per
+ * (sequence, query head). Host only. */
+int yoco_cross_attn_decode_workspace(const yoco_kv_cache* c, int Hq, size_t* bytes, int* splits);
+
+/*
+ * One decode step of a cross-decoder layer (Fig. 3 "Generation"): for every
+ * sequence b one query token; q, o: [B,Hq,d] of the cache dtype. lens: device
+ * int64 [B]; sequence b attends to cache rows [0, lens[b]) -- its own row has
+ * been written before the call (Eq. 2 precedes Eq. 3, the mask is j <= i).
+ * lens[b] is clamped to [0, N_cap]; a sequence with lens[b] == 0 gets zeros.
+ * Pass 1 reduces each split of the cache to (max, sum, vector) for all query
+ * heads of a KV head in one read; pass 2 merges the splits by log-sum-exp in
+ * a fixed order (no atomics: results are bit-reproducible).
+ */
+int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const int64_t* lens, int Hq,
+                           float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Description of the last failure on the calling thread ("" if none). */
+const char* yoco_last_error_string(void);
+
+/* Library version, e.g. 100 = 0.1.0. */
+int yoco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* YOCO_H */

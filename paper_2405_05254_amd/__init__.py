@@ -1,0 +1,11 @@
+"""libyoco: YOCO's attention hot path on MI355X, behind a C ABI.
+
+The Python layer only marshals arguments (torch tensors -> device pointers,
+the current HIP stream); every step of the path runs in the HIP kernels of
+libyoco.so. There is no CPU fallback: a missing library raises.
+"""
+from .binding import (  # noqa: F401
+    F32, BF16, YocoError, KVCache, lib, lib_path,
+    kv_cache_bytes, swa_prefill, global_kv_write, cross_attn_prefill,
+    cross_attn_decode, cross_attn_decode_workspace, version,
+)

@@ -1,0 +1,154 @@
+"""ctypes binding of include/yoco.h: same names, argument marshalling only."""
+import ctypes as C
+import os
+
+import torch
+
+F32, BF16 = 0, 1
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class YocoError(RuntimeError):
+    pass
+
+
+class _Cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("B", C.c_int32), ("Hkv", C.c_int32),
+                ("d", C.c_int32), ("dtype", C.c_int32), ("N_cap", C.c_int64)]
+
+
+def lib_path():
+    return os.path.join(_PKG, "libyoco.so")
+
+
+def lib():
+    """Load libyoco.so (built by paper_2405_05254_amd/build.py); fail loudly if absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise YocoError("libyoco.so is not built: run `python -m paper_2405_05254_amd.build` "
+                        "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_size_t
+    L.yoco_version.restype = i32
+    L.yoco_last_error_string.restype = C.c_char_p
+    L.yoco_kv_cache_bytes.argtypes = [i32, i32, i32, i64, i32, C.POINTER(sz)]
+    L.yoco_kv_cache_init.argtypes = [vp, sz, i32, i32, i32, i64, i32, C.POINTER(_Cache)]
+    L.yoco_swa_prefill.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i64, f32, i32, vp]
+    L.yoco_global_kv_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
+    L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp]
+    L.yoco_cross_attn_decode_workspace.argtypes = [C.POINTER(_Cache), i32, C.POINTER(sz), C.POINTER(i32)]
+    L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
+    for name in ("yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
+                 "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode"):
+        getattr(L, name).restype = i32
+    _LIB = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise YocoError("libyoco error %d: %s" % (rc, lib().yoco_last_error_string().decode()))
+
+
+def _dtype(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise YocoError("unsupported tensor dtype %s" % t.dtype)
+
+
+def _dev(t, name):
+    if not t.is_cuda:
+        raise YocoError("%s must be a device tensor" % name)
+    if not t.is_contiguous():
+        raise YocoError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def version():
+    return lib().yoco_version()
+
+
+def kv_cache_bytes(B, Hkv, d, N_cap, dtype):
+    n = C.c_size_t()
+    _check(lib().yoco_kv_cache_bytes(B, Hkv, d, N_cap, dtype, C.byref(n)))
+    return n.value
+
+
+class KVCache:
+    """The once-only global K^/V^ cache: torch owns the memory, the descriptor is yoco_kv_cache."""
+
+    def __init__(self, B, Hkv, d, N_cap, dtype=torch.bfloat16, device="cuda"):
+        code = F32 if dtype == torch.float32 else BF16
+        self.bytes = kv_cache_bytes(B, Hkv, d, N_cap, code)
+        self.mem = torch.empty(self.bytes, dtype=torch.uint8, device=device)
+        self.desc = _Cache()
+        _check(lib().yoco_kv_cache_init(self.mem.data_ptr(), self.bytes, B, Hkv, d, N_cap, code, C.byref(self.desc)))
+        self.B, self.Hkv, self.d, self.N_cap, self.dtype = B, Hkv, d, N_cap, dtype
+
+    def planes(self):
+        """Views [B,Hkv,N_cap,d] of the K and V planes (for tests and for filling synthetic caches)."""
+        half = self.bytes // 2
+        shape = (self.B, self.Hkv, self.N_cap, self.d)
+        return (self.mem[:half].view(self.dtype).view(shape), self.mem[half:].view(self.dtype).view(shape))
+
+
+def swa_prefill(q, k, v, window, scale, out=None):
+    """q [B,T,Hq,d]; k, v [B,T,Hkv,d] -> o [B,T,Hq,d] (yoco_swa_prefill)."""
+    B, T, Hq, d = q.shape
+    Hkv = k.shape[2]
+    if k.shape != (B, T, Hkv, d) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise YocoError("q/k/v shapes or dtypes disagree")
+    o = torch.empty_like(q) if out is None else out
+    _check(lib().yoco_swa_prefill(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(o, "o"), B, T, Hq, Hkv, d,
+                                  window, scale, _dtype(q), _stream()))
+    return o
+
+
+def global_kv_write(cache, k, v, b, pos0):
+    """k, v [n,Hkv,d] rows -> cache rows [pos0, pos0+n) of sequence b (yoco_global_kv_write)."""
+    n = k.shape[0]
+    if n and (k.shape != (n, cache.Hkv, cache.d) or v.shape != k.shape or v.dtype != k.dtype):
+        raise YocoError("k/v rows do not match the cache")
+    _check(lib().yoco_global_kv_write(C.byref(cache.desc), _dev(k, "k") if n else None, _dev(v, "v") if n else None,
+                                      b, pos0, n, _dtype(k), _stream()))
+
+
+def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None):
+    """q [Tq,Hq,d] -> o [Tq,Hq,d], causal over the cache of sequence b (yoco_cross_attn_prefill)."""
+    Tq, Hq, d = q.shape
+    if d != cache.d or q.dtype != cache.dtype:
+        raise YocoError("q does not match the cache")
+    o = torch.empty_like(q) if out is None else out
+    _check(lib().yoco_cross_attn_prefill(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), b, q_pos0, Tq, Hq, scale,
+                                         _stream()))
+    return o
+
+
+def cross_attn_decode_workspace(cache, Hq):
+    n, s = C.c_size_t(), C.c_int()
+    _check(lib().yoco_cross_attn_decode_workspace(C.byref(cache.desc), Hq, C.byref(n), C.byref(s)))
+    return n.value, s.value
+
+
+def cross_attn_decode(cache, q, lens, scale, workspace, out=None):
+    """q [B,Hq,d], lens int64 [B] (device) -> o [B,Hq,d] (yoco_cross_attn_decode)."""
+    B, Hq, d = q.shape
+    if B != cache.B or d != cache.d or q.dtype != cache.dtype:
+        raise YocoError("q does not match the cache")
+    if lens.dtype != torch.int64 or lens.shape != (B,):
+        raise YocoError("lens must be int64 [B]")
+    o = torch.empty_like(q) if out is None else out
+    _check(lib().yoco_cross_attn_decode(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq,
+                                        scale, _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                        _stream()))
+    return o

@@ -1,0 +1,207 @@
+// C ABI of libyoco: argument validation and dispatch. No device code here.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "yoco_common.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) return YOCO_OK;
+  return fail(YOCO_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+size_t elem_bytes(int dtype) { return dtype == YOCO_F32 ? 4 : 2; }
+bool dtype_ok(int dtype) { return dtype == YOCO_F32 || dtype == YOCO_BF16; }
+
+int check_cache(const yoco_kv_cache* c) {
+  if (!c) return fail(YOCO_ERR_INVALID_ARG, "cache descriptor is null");
+  if (!c->k || !c->v) return fail(YOCO_ERR_INVALID_ARG, "cache planes are null");
+  if (c->B <= 0 || c->Hkv <= 0 || c->N_cap <= 0) return fail(YOCO_ERR_INVALID_ARG, "cache has a non-positive size");
+  if (!dtype_ok(c->dtype)) return fail(YOCO_ERR_UNSUPPORTED, "cache dtype %d", c->dtype);
+  if (c->d <= 0 || c->d > 256) return fail(YOCO_ERR_UNSUPPORTED, "head_dim %d not in [8, 256]", c->d);
+  if (c->d % 8) return fail(YOCO_ERR_ALIGNMENT, "head_dim %d is not a multiple of 8", c->d);
+  if (!aligned16(c->k) || !aligned16(c->v)) return fail(YOCO_ERR_ALIGNMENT, "cache planes are not 16-byte aligned");
+  return YOCO_OK;
+}
+
+int check_heads(int Hq, int Hkv) {
+  if (Hq <= 0 || Hkv <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive head count");
+  if (Hq % Hkv) return fail(YOCO_ERR_INVALID_ARG, "Hq %d is not a multiple of Hkv %d", Hq, Hkv);
+  if (Hq > 65535) return fail(YOCO_ERR_UNSUPPORTED, "Hq %d exceeds the grid limit", Hq);
+  return YOCO_OK;
+}
+
+// Splits of the decode pass: enough workgroups to fill 256 CUs several times
+// over, but at least 256 cache rows per split.
+int decode_splits(const yoco_kv_cache* c) {
+  const int64_t units = (int64_t)c->B * c->Hkv;
+  int64_t s = (2048 + units - 1) / units;
+  const int64_t by_rows = (c->N_cap + 255) / 256;
+  if (s > by_rows) s = by_rows;
+  if (s < 1) s = 1;
+  if (s > 1024) s = 1024;
+  return (int)s;
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int yoco_version(void) { return 100; }
+
+const char* yoco_last_error_string(void) { return g_err; }
+
+int yoco_kv_cache_bytes(int B, int Hkv, int d, int64_t N_cap, int dtype, size_t* bytes) {
+  if (!bytes) return fail(YOCO_ERR_INVALID_ARG, "bytes is null");
+  if (B <= 0 || Hkv <= 0 || d <= 0 || N_cap <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive size");
+  if (!dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (d % 8) return fail(YOCO_ERR_ALIGNMENT, "head_dim %d is not a multiple of 8", d);
+  if (d > 256) return fail(YOCO_ERR_UNSUPPORTED, "head_dim %d exceeds 256", d);
+  *bytes = (size_t)2 * B * Hkv * (size_t)N_cap * d * elem_bytes(dtype);
+  return YOCO_OK;
+}
+
+int yoco_kv_cache_init(void* mem, size_t bytes, int B, int Hkv, int d, int64_t N_cap, int dtype, yoco_kv_cache* out) {
+  if (!out) return fail(YOCO_ERR_INVALID_ARG, "out is null");
+  if (!mem) return fail(YOCO_ERR_INVALID_ARG, "mem is null");
+  size_t need = 0;
+  int rc = yoco_kv_cache_bytes(B, Hkv, d, N_cap, dtype, &need);
+  if (rc) return rc;
+  if (bytes < need) return fail(YOCO_ERR_WORKSPACE, "cache memory %zu < %zu bytes", bytes, need);
+  if (((uintptr_t)mem) & 255u) return fail(YOCO_ERR_ALIGNMENT, "cache memory is not 256-byte aligned");
+  out->k = mem;
+  out->v = (char*)mem + need / 2;
+  out->B = B;
+  out->Hkv = Hkv;
+  out->d = d;
+  out->dtype = dtype;
+  out->N_cap = N_cap;
+  return YOCO_OK;
+}
+
+int yoco_swa_prefill(const void* q, const void* k, const void* v, void* o, int B, int64_t T, int Hq, int Hkv, int d,
+                     int64_t window, float scale, int dtype, void* stream) {
+  if (!q || !k || !v || !o) return fail(YOCO_ERR_INVALID_ARG, "null tensor pointer");
+  if (B <= 0 || T <= 0 || window <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive B, T or window");
+  if (B > 65535) return fail(YOCO_ERR_UNSUPPORTED, "B %d exceeds the grid limit", B);
+  int rc = check_heads(Hq, Hkv);
+  if (rc) return rc;
+  if (!dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (d <= 0 || d > 256) return fail(YOCO_ERR_UNSUPPORTED, "head_dim %d not in [8, 256]", d);
+  if (d % 8) return fail(YOCO_ERR_ALIGNMENT, "head_dim %d is not a multiple of 8", d);
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+    return fail(YOCO_ERR_ALIGNMENT, "tensor pointer not 16-byte aligned");
+  yoco::AttnView a;
+  a.q = q; a.k = k; a.v = v; a.o = o;
+  a.q_stride_t = (int64_t)Hq * d;
+  a.q_stride_b = T * a.q_stride_t;
+  a.kv_stride_n = (int64_t)Hkv * d;
+  a.kv_stride_h = d;
+  a.kv_stride_b = T * a.kv_stride_n;
+  a.Tq = T; a.q_pos0 = 0;
+  a.window = window > T ? T : window;
+  a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.B = B; a.scale = scale;
+  if (yoco::swa_mfma_supported(a, dtype)) return hip_result(yoco::launch_swa_mfma(a, (hipStream_t)stream), "swa_prefill");
+  return hip_result(yoco::launch_attn_generic(a, dtype, (hipStream_t)stream), "swa_prefill");
+}
+
+int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+                         int src_dtype, void* stream) {
+  int rc = check_cache(c);
+  if (rc) return rc;
+  if (n < 0) return fail(YOCO_ERR_INVALID_ARG, "negative row count");
+  if (b < 0 || b >= c->B) return fail(YOCO_ERR_INVALID_ARG, "sequence %d outside [0, %d)", b, c->B);
+  if (pos0 < 0 || pos0 + n > c->N_cap)
+    return fail(YOCO_ERR_INVALID_ARG, "rows [%lld, %lld) outside the cache capacity %lld", (long long)pos0,
+                (long long)(pos0 + n), (long long)c->N_cap);
+  if (!dtype_ok(src_dtype)) return fail(YOCO_ERR_UNSUPPORTED, "source dtype %d", src_dtype);
+  if (n == 0) return YOCO_OK;
+  if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
+  if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
+  return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
+}
+
+int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0, int64_t Tq, int Hq,
+                            float scale, void* stream) {
+  int rc = check_cache(c);
+  if (rc) return rc;
+  rc = check_heads(Hq, c->Hkv);
+  if (rc) return rc;
+  if (!q || !o) return fail(YOCO_ERR_INVALID_ARG, "null tensor pointer");
+  if (!aligned16(q) || !aligned16(o)) return fail(YOCO_ERR_ALIGNMENT, "tensor pointer not 16-byte aligned");
+  if (b < 0 || b >= c->B) return fail(YOCO_ERR_INVALID_ARG, "sequence %d outside [0, %d)", b, c->B);
+  if (Tq <= 0 || q_pos0 < 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive Tq or negative q_pos0");
+  if (q_pos0 + Tq > c->N_cap)
+    return fail(YOCO_ERR_INVALID_ARG, "query positions up to %lld exceed the cache capacity %lld",
+                (long long)(q_pos0 + Tq), (long long)c->N_cap);
+  const size_t eb = elem_bytes(c->dtype);
+  const int64_t plane_b = (int64_t)c->Hkv * c->N_cap * c->d;
+  yoco::AttnView a;
+  a.q = q; a.o = o;
+  a.k = (const char*)c->k + (size_t)b * plane_b * eb;
+  a.v = (const char*)c->v + (size_t)b * plane_b * eb;
+  a.q_stride_t = (int64_t)Hq * c->d;
+  a.q_stride_b = 0;
+  a.kv_stride_n = c->d;
+  a.kv_stride_h = c->N_cap * c->d;
+  a.kv_stride_b = 0;
+  a.Tq = Tq; a.q_pos0 = q_pos0;
+  a.window = q_pos0 + Tq;          // every earlier row is visible
+  a.Hq = Hq; a.Hkv = c->Hkv; a.d = c->d; a.B = 1; a.scale = scale;
+  if (yoco::swa_mfma_supported(a, c->dtype))
+    return hip_result(yoco::launch_swa_mfma(a, (hipStream_t)stream), "cross_attn_prefill");
+  return hip_result(yoco::launch_attn_generic(a, c->dtype, (hipStream_t)stream), "cross_attn_prefill");
+}
+
+int yoco_cross_attn_decode_workspace(const yoco_kv_cache* c, int Hq, size_t* bytes, int* splits) {
+  if (!c || !bytes || !splits) return fail(YOCO_ERR_INVALID_ARG, "null argument");
+  if (c->B <= 0 || c->Hkv <= 0 || c->N_cap <= 0 || c->d <= 0) return fail(YOCO_ERR_INVALID_ARG, "cache has a non-positive size");
+  int rc = check_heads(Hq, c->Hkv);
+  if (rc) return rc;
+  const int s = decode_splits(c);
+  *splits = s;
+  *bytes = (size_t)c->B * Hq * s * yoco::partial_stride(c->d) * sizeof(float);
+  return YOCO_OK;
+}
+
+int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const int64_t* lens, int Hq, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_cache(c);
+  if (rc) return rc;
+  rc = check_heads(Hq, c->Hkv);
+  if (rc) return rc;
+  if (!q || !o || !lens || !workspace) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(q) || !aligned16(o) || !aligned16(workspace))
+    return fail(YOCO_ERR_ALIGNMENT, "pointer not 16-byte aligned");
+  if (c->B > 65535) return fail(YOCO_ERR_UNSUPPORTED, "B %d exceeds the grid limit", c->B);
+  size_t need = 0;
+  int splits = 0;
+  rc = yoco_cross_attn_decode_workspace(c, Hq, &need, &splits);
+  if (rc) return rc;
+  if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t e;
+  if (yoco::decode_bf16_supported(*c, Hq))
+    e = yoco::launch_decode_bf16(*c, q, lens, Hq, scale, (float*)workspace, splits, s);
+  else
+    e = yoco::launch_decode_generic(*c, q, o, lens, Hq, scale, (float*)workspace, splits, s);
+  if (e != hipSuccess) return hip_result(e, "cross_attn_decode pass 1");
+  return hip_result(yoco::launch_decode_merge((const float*)workspace, o, c->B, Hq, c->d, splits, c->dtype, s),
+                    "cross_attn_decode merge");
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

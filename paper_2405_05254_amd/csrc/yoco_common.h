@@ -1,0 +1,66 @@
+// Shared declarations of libyoco's translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "yoco.h"
+
+namespace yoco {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float x) { *p = f32_to_bf16(x); }
+};
+
+// Addressing of one attention problem family. Strides are in elements.
+struct AttnView {
+  const void* q;   // [.., Tq, Hq, d]
+  const void* k;
+  const void* v;
+  void* o;         // [.., Tq, Hq, d]
+  int64_t q_stride_b, q_stride_t;          // o uses the same strides
+  int64_t kv_stride_b, kv_stride_h, kv_stride_n;
+  int64_t Tq;       // query rows per sequence
+  int64_t q_pos0;   // absolute position of query row 0
+  int64_t window;   // keys visible per row (>= 1); INT64_MAX/2 = unbounded
+  int Hq, Hkv, d, B;
+  float scale;
+};
+
+// Launchers (each returns the hipError_t of its launch).
+hipError_t launch_attn_generic(const AttnView& a, int dtype, hipStream_t s);
+hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, void* o, const int64_t* lens, int Hq,
+                                 float scale, float* ws, int splits, hipStream_t s);
+hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, int splits, int dtype,
+                               hipStream_t s);
+hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+                           int src_dtype, hipStream_t s);
+
+// bf16, d = 128 fast paths. `supported` functions are host-side predicates.
+bool swa_mfma_supported(const AttnView& a, int dtype);
+hipError_t launch_swa_mfma(const AttnView& a, hipStream_t s);
+bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
+hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int Hq, float scale,
+                              float* ws, int splits, hipStream_t s);
+
+// Partial result of one split: [m, l, o[0..d)] floats per (b, h, split).
+__host__ __device__ inline size_t partial_stride(int d) { return (size_t)d + 2; }
+
+}  // namespace yoco

@@ -1,0 +1,109 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/yoco.h declares, sizes the cache as the paper's Table 1
+says (one K/V pair per token whatever the depth), and rejects bad arguments
+before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2405_05254_amd as yoco
+from paper_2405_05254_amd import binding as yb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "yoco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(yoco_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = yoco.lib()
+    names = declared_symbols()
+    assert {"yoco_swa_prefill", "yoco_global_kv_write", "yoco_cross_attn_prefill", "yoco_cross_attn_decode"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert yoco.version() >= 100
+
+
+def test_cache_bytes_follow_table_1():
+    # bytes per token = 2 * Hkv * d * sizeof, independent of the number of layers
+    assert yoco.kv_cache_bytes(1, 8, 128, 1, yoco.BF16) == 4096
+    assert yoco.kv_cache_bytes(1, 8, 128, 524288, yoco.BF16) == 2147483648     # 512K-token cache
+    assert yoco.kv_cache_bytes(16, 8, 128, 32768, yoco.BF16) == 2147483648     # 16 x 32K
+    assert yoco.kv_cache_bytes(1, 16, 128, 131072, yoco.BF16) == 1073741824
+    assert yoco.kv_cache_bytes(1, 1, 64, 512, yoco.F32) == 2 * 512 * 64 * 4
+    # the paper's 65B example (section 4.4): 128K tokens per GiB
+    assert 2 ** 30 // yoco.kv_cache_bytes(1, 16, 128, 1, yoco.BF16) == 131072
+
+
+def test_cache_init_fills_descriptor_and_checks_memory():
+    L = yoco.lib()
+    d = yb._Cache()
+    need = yoco.kv_cache_bytes(2, 4, 64, 100, yoco.BF16)
+    base = 0x7f0000000000          # never dereferenced by the host-only call
+    assert L.yoco_kv_cache_init(base, need, 2, 4, 64, 100, yoco.BF16, C.byref(d)) == 0
+    assert d.k == base and d.v == base + need // 2 and (d.B, d.Hkv, d.d, d.N_cap) == (2, 4, 64, 100)
+    assert L.yoco_kv_cache_init(base, need - 1, 2, 4, 64, 100, yoco.BF16, C.byref(d)) == -4
+    assert b"cache memory" in L.yoco_last_error_string()
+    assert L.yoco_kv_cache_init(base + 16, need, 2, 4, 64, 100, yoco.BF16, C.byref(d)) == -3
+    assert L.yoco_kv_cache_init(None, need, 2, 4, 64, 100, yoco.BF16, C.byref(d)) == -1
+
+
+@pytest.mark.parametrize("args,code", [
+    ((0, 8, 128, 10, 1), -1), ((1, 8, 128, 0, 1), -1), ((1, 8, 12, 10, 1), -3),
+    ((1, 8, 512, 10, 1), -2), ((1, 8, 128, 10, 7), -2),
+])
+def test_cache_bytes_rejects_bad_sizes(args, code):
+    n = C.c_size_t()
+    assert yoco.lib().yoco_kv_cache_bytes(*args, C.byref(n)) == code
+    assert yoco.lib().yoco_last_error_string() != b""
+
+
+def test_calls_validate_before_launching():
+    """Every failure below is found on the host: nothing reaches the GPU (there is none here)."""
+    L = yoco.lib()
+    p = 0x7f0000000000
+    # swa_prefill
+    assert L.yoco_swa_prefill(None, p, p, p, 1, 8, 4, 4, 64, 4, 1.0, 0, None) == -1
+    assert L.yoco_swa_prefill(p, p, p, p, 1, 8, 6, 4, 64, 4, 1.0, 0, None) == -1      # Hq % Hkv
+    assert L.yoco_swa_prefill(p, p, p, p, 1, 8, 4, 4, 64, 0, 1.0, 0, None) == -1      # window 0
+    assert L.yoco_swa_prefill(p, p, p, p, 1, 0, 4, 4, 64, 4, 1.0, 0, None) == -1      # T 0
+    assert L.yoco_swa_prefill(p, p + 4, p, p, 1, 8, 4, 4, 64, 4, 1.0, 0, None) == -3  # alignment
+    assert L.yoco_swa_prefill(p, p, p, p, 1, 8, 4, 4, 60, 4, 1.0, 0, None) == -3      # d % 8
+    assert L.yoco_swa_prefill(p, p, p, p, 1, 8, 4, 4, 64, 4, 1.0, 5, None) == -2      # dtype
+    d = yb._Cache()
+    need = yoco.kv_cache_bytes(2, 2, 64, 100, yoco.BF16)
+    assert L.yoco_kv_cache_init(p, need, 2, 2, 64, 100, yoco.BF16, C.byref(d)) == 0
+    # global_kv_write
+    assert L.yoco_global_kv_write(C.byref(d), p, p, 2, 0, 1, 1, None) == -1            # b out of range
+    assert L.yoco_global_kv_write(C.byref(d), p, p, 0, 99, 2, 1, None) == -1           # beyond capacity
+    assert L.yoco_global_kv_write(C.byref(d), p, p, 0, -1, 1, 1, None) == -1
+    assert L.yoco_global_kv_write(C.byref(d), None, None, 0, 5, 0, 1, None) == 0       # empty write is a no-op
+    assert L.yoco_global_kv_write(None, p, p, 0, 0, 1, 1, None) == -1
+    # cross_attn_prefill
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 98, 4, 4, 1.0, None) == -1   # beyond capacity
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 0, 4, 1.0, None) == -1
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 4, 3, 1.0, None) == -1    # Hq % Hkv
+    # decode: workspace sizing and checks
+    n, s = C.c_size_t(), C.c_int()
+    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(n), C.byref(s)) == 0
+    assert s.value >= 1 and n.value == 2 * 4 * s.value * (64 + 2) * 4
+    assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 4, 1.0, p, n.value - 1, None) == -4
+    assert L.yoco_cross_attn_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
+    assert b"null" in L.yoco_last_error_string()
+
+
+def test_decode_splits_fill_the_chip():
+    L = yoco.lib()
+    p = 0x7f0000000000
+    for B, N in ((1, 524288), (16, 32768)):
+        d = yb._Cache()
+        assert L.yoco_kv_cache_init(p, yoco.kv_cache_bytes(B, 8, 128, N, yoco.BF16), B, 8, 128, N, yoco.BF16, C.byref(d)) == 0
+        n, s = C.c_size_t(), C.c_int()
+        assert L.yoco_cross_attn_decode_workspace(C.byref(d), 24, C.byref(n), C.byref(s)) == 0
+        assert B * 8 * s.value >= 1024          # several workgroups per CU (256 CUs)
+        assert n.value < 0.01 * 2 * B * 8 * N * 128 * 2   # partials cost < 1 % of the cache bytes
