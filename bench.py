@@ -1,0 +1,173 @@
+"""Benchmark of libyoco on one MI355X.
+
+One "step" is one pass of the whole attention hot path over one synthetic
+batch at the headline shape (T=32768, 24 query heads x 128, window 1024):
+  SWA prefill (24 KV heads)  ->  global K^/V^ write of the T rows (8 KV heads)
+  ->  cross-attention prefill of the last position  ->  one split-KV decode
+  step (pass 1 + log-sum-exp merge) over that cache.
+`value` is T / step time. The roofline object is for the dominant kernel, the
+SWA prefill (algorithmic flops = 4 * d * unmasked (query, key) pairs). The two
+decode workloads the metric also names (16 x 32K and 1 x 512K caches, 13
+cross-decoder layers back to back) are timed in the same run and reported
+under "decode" as GB/s against the HBM peak. The fp64 oracle is timed on a
+bounded sample of the same SWA workload on the host cores ("cpu_baseline").
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2516.6    # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def swa_flops(T, H, d, C):
+    pairs = C * (C + 1) // 2 + (T - C) * C if T > C else T * (T + 1) // 2
+    return 4.0 * d * pairs * H
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-decode", action="store_true", help="skip the two decode workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2405_05254_amd as yoco
+    import yoco_synth as ys
+
+    yoco.lib()                                   # no library, no benchmark: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    c = ys.CONFIGS["swa_prefill_32k"]
+    T, H, d, C = c["T"], c["Hq"], c["d"], c["window"]
+    Hkv_cache = ys.CONFIGS["decode_b16_32k"]["Hkv"]
+    scale = 1.0 / math.sqrt(d)
+
+    # ---- inputs, resident in HBM before any timing
+    qn, kn, vn = ys.qkv(c["seed"], T, H, H, d, c["std"], "bf16")
+    q, k, v = (torch.from_numpy(x[None]).to(dev).to(torch.bfloat16) for x in (qn, kn, vn))
+    o = torch.empty_like(q)
+    khat = ys.device_normal((T, Hkv_cache, d), 11, 1.0, torch.bfloat16, dev)
+    vhat = ys.device_normal((T, Hkv_cache, d), 12, 1.0, torch.bfloat16, dev)
+    cache = yoco.KVCache(1, Hkv_cache, d, T, torch.bfloat16)
+    q_last = ys.device_normal((1, H, d), 13, 1.0, torch.bfloat16, dev)
+    o_last = torch.empty_like(q_last)
+    o_dec = torch.empty_like(q_last)
+    lens = torch.tensor([T], dtype=torch.int64, device=dev)
+    nbytes, _ = yoco.cross_attn_decode_workspace(cache, H)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        yoco.swa_prefill(q, k, v, C, scale, out=o)
+        if ev:
+            ev[1].record()
+        yoco.global_kv_write(cache, khat, vhat, 0, 0)
+        yoco.cross_attn_prefill(cache, q_last, 0, T - 1, scale, out=o_last)
+        yoco.cross_attn_decode(cache, q_last, lens, scale, ws, out=o_dec)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+    flops = swa_flops(T, H, d, C)
+    swa_tflops = flops / (swa_ms * 1e-3) / 1e12
+
+    # ---- the decode workloads of the metric: 13 cross-decoder layers over one shared cache
+    decode = {}
+    if not args.no_decode:
+        del q, k, v, o
+        for name in ("decode_b16_32k", "decode_b1_512k"):
+            dc = ys.CONFIGS[name]
+            B, N, Hq, Hkv, layers = dc["B"], dc["N"], dc["Hq"], dc["Hkv"], dc["layers"]
+            kvc = yoco.KVCache(B, Hkv, d, N, torch.bfloat16)
+            Kp, Vp = kvc.planes()
+            Kp.copy_(ys.device_normal(Kp.shape, dc["seed"], dc["std"], torch.bfloat16, dev))
+            Vp.copy_(ys.device_normal(Vp.shape, dc["seed"] + 1, dc["std"], torch.bfloat16, dev))
+            qs = [ys.device_normal((B, Hq, d), 100 + i, dc["std"], torch.bfloat16, dev) for i in range(layers)]
+            od = torch.empty_like(qs[0])
+            ln = torch.full((B,), N, dtype=torch.int64, device=dev)
+            nb, splits = yoco.cross_attn_decode_workspace(kvc, Hq)
+            w = torch.empty(nb, dtype=torch.uint8, device=dev)
+            reps = max(3, args.steps // 2)
+            times = []
+            for rep in range(2 + reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(layers):
+                    yoco.cross_attn_decode(kvc, qs[i], ln, scale, w, out=od)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep >= 2:
+                    times.append(e0.elapsed_time(e1))
+            ms = sum(times) / len(times)
+            cache_bytes = 2.0 * B * N * Hkv * d * 2
+            gbs = layers * cache_bytes / (ms * 1e-3) / 1e9
+            decode[name] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4), min_ms=round(min(times), 4),
+                                GBps=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), splits=splits,
+                                cache_bytes=int(cache_bytes))
+            del kvc, Kp, Vp, w, qs
+            torch.cuda.empty_cache()
+
+    # ---- the oracle on the host cores, bounded sample of the same SWA workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        rng = np.random.default_rng(1)
+        n, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < args.cpu_seconds:
+            for _ in range(64):
+                oracle.swa_row(qn, kn, vn, int(rng.integers(C, T)), int(rng.integers(0, H)), C, scale)
+            n += 64
+        dt = time.perf_counter() - t0
+        cpu = dict(value=round(n / H / dt, 3), unit="tokens/s", cores=cores, kind="oracle",
+                   sample="%d sampled (row, head) outputs of the same T=32768 x 24-head SWA workload in %.1f s; "
+                          "a token = 24 head rows" % (n, dt))
+
+    out = {
+        "metric": "swa_prefill_tokens_per_s", "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "swa_prefill_32k: B=1 T=32768 24x128 heads window 1024 (+ K^/V^ write of T rows x 8 KV heads, "
+                               "last-token cross-attention, one split-KV decode step)", "seed": c["seed"]},
+        "swa_prefill": {"ms": round(swa_ms, 4), "tokens_per_s": round(T / (swa_ms * 1e-3), 1),
+                        "TFLOPs": round(swa_tflops, 1), "frac_of_mfma_peak": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "roofline": {"kernel": "yoco_swa_prefill", "bound": "mfma", "achieved": round(swa_tflops, 1),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None},
+        "decode": decode,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

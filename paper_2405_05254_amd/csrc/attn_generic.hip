@@ -127,11 +127,11 @@ __global__ void __launch_bounds__(64) decode_generic_kernel(yoco_kv_cache c, con
   if (j_lo <= j_hi)
     attend_range<T>((const T*)c.k + head_off, (const T*)c.v + head_off, d, j_lo, j_hi, d, scale, q_s, p_s, m, l, acc);
   float* w = ws + (((size_t)b * Hq + h) * splits + sp) * partial_stride(d);
-  if (lane == 0) { w[0] = m; w[1] = l; }
+  if (lane == 0) { w[d] = m; w[d + 1] = l; }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int e = lane + 64 * t;
-    if (e < d) w[2 + e] = acc[t];
+    if (e < d) w[e] = acc[t];
   }
 }
 
@@ -146,46 +146,73 @@ hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, void* /*
 }
 
 // ---- decode, pass 2: merge the splits of one (sequence, query head) by
-// log-sum-exp in split order. o = sum_s e^{m_s-M} o_s / sum_s e^{m_s-M} l_s.
+// log-sum-exp: o = sum_s e^{m_s-M} o_s / sum_s e^{m_s-M} l_s.
+// Phase 1 finds M, phase 2 puts the factors e^{m_s-M} in LDS, phase 3 has
+// thread (sl, dl) add splits sl, sl+nsl, ... for dimensions 4dl..4dl+3 with
+// independent 128-bit loads; the nsl partial sums are then added in order.
+// Assignment and order are fixed (no atomics): results are bit-reproducible.
+constexpr int kMaxSplits = 1024;
+
 template <typename T>
-__global__ void __launch_bounds__(64) decode_merge_kernel(const float* __restrict__ ws, T* __restrict__ o, int d,
-                                                          int splits) {
-  const int lane = threadIdx.x;
+__global__ void __launch_bounds__(256) decode_merge_kernel(const float* __restrict__ ws, T* __restrict__ o, int d,
+                                                           int splits) {
+  __shared__ float sF[kMaxSplits];
+  __shared__ float sRed[8];
+  __shared__ __attribute__((aligned(16))) float sO[1024];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const size_t bh = blockIdx.x;
-  const float* w = ws + bh * splits * partial_stride(d);
+  const size_t ps = partial_stride(d);
+  const float* w = ws + bh * splits * ps;
   float M = -INFINITY;
-  for (int s = lane; s < splits; s += 64) M = fmaxf(M, w[s * partial_stride(d)]);
+  for (int s = tid; s < splits; s += 256) M = fmaxf(M, w[s * ps + d]);
   M = wave_max(M);
-  float acc[4] = {0.f, 0.f, 0.f, 0.f}, L = 0.f;
-  if (M > -INFINITY) {
-    for (int s = 0; s < splits; ++s) {
-      const float* ps = w + s * partial_stride(d);
-      const float ms = ps[0];
-      if (ms == -INFINITY) continue;            // empty split
-      const float f = __expf(ms - M);
-      L = fmaf(f, ps[1], L);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int e = lane + 64 * t;
-        if (e < d) acc[t] = fmaf(f, ps[2 + e], acc[t]);
-      }
-    }
+  if (lane == 0) sRed[wave] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(sRed[0], sRed[1]), fmaxf(sRed[2], sRed[3]));
+  float L = 0.f;
+  for (int s = tid; s < splits; s += 256) {
+    const float ms = w[s * ps + d];
+    const float f = (ms == -INFINITY) ? 0.f : __expf(ms - M);        // empty split (or no row at all)
+    sF[s] = f;
+    L = fmaf(f, w[s * ps + d + 1], L);
   }
-  const float inv = (L > 0.f) ? 1.f / L : 0.f;   // no visible row -> zeros
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int e = lane + 64 * t;
-    if (e < d) Elem<T>::store(o + bh * d + e, acc[t] * inv);
+  L = wave_sum(L);
+  if (lane == 0) sRed[4 + wave] = L;
+  __syncthreads();
+  L = ((sRed[4] + sRed[5]) + sRed[6]) + sRed[7];
+  const int nd = d >> 2;               // 128-bit groups per row
+  const int nsl = 256 / nd;            // split lanes
+  const int sl = tid / nd, dl = tid - sl * nd;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (sl < nsl) {
+#pragma unroll 4
+    for (int s = sl; s < splits; s += nsl) {
+      const float f = sF[s];
+      const float4 x = *(const float4*)(w + s * ps + 4 * dl);
+      acc.x = fmaf(f, x.x, acc.x);
+      acc.y = fmaf(f, x.y, acc.y);
+      acc.z = fmaf(f, x.z, acc.z);
+      acc.w = fmaf(f, x.w, acc.w);
+    }
+    *(float4*)(sO + sl * d + 4 * dl) = acc;
+  }
+  __syncthreads();
+  const float inv = (L > 0.f) ? 1.f / L : 0.f;                        // no visible row -> zeros
+  for (int e = tid; e < d; e += 256) {
+    float x = 0.f;
+    for (int k = 0; k < nsl; ++k) x += sO[k * d + e];
+    Elem<T>::store(o + bh * d + e, x * inv);
   }
 }
 
 hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, int splits, int dtype,
                                hipStream_t s) {
+  if (splits > kMaxSplits) return hipErrorInvalidValue;
   dim3 grid((unsigned)(B * Hq));
   if (dtype == YOCO_F32)
-    hipLaunchKernelGGL(decode_merge_kernel<float>, grid, dim3(64), 0, s, ws, (float*)o, d, splits);
+    hipLaunchKernelGGL(decode_merge_kernel<float>, grid, dim3(256), 0, s, ws, (float*)o, d, splits);
   else
-    hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, grid, dim3(64), 0, s, ws, (bf16_t*)o, d, splits);
+    hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, grid, dim3(256), 0, s, ws, (bf16_t*)o, d, splits);
   return hipGetLastError();
 }
 

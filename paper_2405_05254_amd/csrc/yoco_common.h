@@ -60,7 +60,8 @@ bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int Hq, float scale,
                               float* ws, int splits, hipStream_t s);
 
-// Partial result of one split: [m, l, o[0..d)] floats per (b, h, split).
-__host__ __device__ inline size_t partial_stride(int d) { return (size_t)d + 2; }
+// Partial result of one split, per (b, h, split): o[0..d), then the running max
+// m (natural-log units) and sum l, padded so every row starts 16-byte aligned.
+__host__ __device__ inline size_t partial_stride(int d) { return (size_t)d + 4; }
 
 }  // namespace yoco

@@ -91,7 +91,7 @@ def test_calls_validate_before_launching():
     # decode: workspace sizing and checks
     n, s = C.c_size_t(), C.c_int()
     assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(n), C.byref(s)) == 0
-    assert s.value >= 1 and n.value == 2 * 4 * s.value * (64 + 2) * 4
+    assert s.value >= 1 and n.value == 2 * 4 * s.value * (64 + 4) * 4
     assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 4, 1.0, p, n.value - 1, None) == -4
     assert L.yoco_cross_attn_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
     assert b"null" in L.yoco_last_error_string()
@@ -105,5 +105,5 @@ def test_decode_splits_fill_the_chip():
         assert L.yoco_kv_cache_init(p, yoco.kv_cache_bytes(B, 8, 128, N, yoco.BF16), B, 8, 128, N, yoco.BF16, C.byref(d)) == 0
         n, s = C.c_size_t(), C.c_int()
         assert L.yoco_cross_attn_decode_workspace(C.byref(d), 24, C.byref(n), C.byref(s)) == 0
-        assert B * 8 * s.value >= 1024          # several workgroups per CU (256 CUs)
+        assert B * 8 * s.value >= 256           # at least one workgroup per CU (256 CUs)
         assert n.value < 0.01 * 2 * B * 8 * N * 128 * 2   # partials cost < 1 % of the cache bytes
