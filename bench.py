@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-decode", action="store_true", help="skip the two decode workloads")
+    ap.add_argument("--only", choices=["all", "swa", "decode"], default="all",
+                    help="profiling aid: 'swa' runs only the SWA prefill launches, 'decode' only the decode workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -72,12 +74,21 @@ def main():
     nbytes, _ = yoco.cross_attn_decode_workspace(cache, H)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
+    if args.only != "all":
+        args.no_cpu_baseline = True
+    if args.only == "swa":
+        args.no_decode = True
+
     def step(ev=None):
+        if args.only == "decode":
+            return
         if ev:
             ev[0].record()
         yoco.swa_prefill(q, k, v, C, scale, out=o)
         if ev:
             ev[1].record()
+        if args.only == "swa":
+            return
         yoco.global_kv_write(cache, khat, vhat, 0, 0)
         yoco.cross_attn_prefill(cache, q_last, 0, T - 1, scale, out=o_last)
         yoco.cross_attn_decode(cache, q_last, lens, scale, ws, out=o_dec)
@@ -92,7 +103,7 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps if args.only != "decode" else float("nan")
     flops = swa_flops(T, H, d, C)
     swa_tflops = flops / (swa_ms * 1e-3) / 1e12
 

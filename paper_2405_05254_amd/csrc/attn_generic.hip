@@ -216,7 +216,41 @@ hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, i
   return hipGetLastError();
 }
 
-// ---- global KV write: rows [n,Hkv,d] -> planes [B][Hkv][N_cap][d] of the cache dtype.
+// ---- global KV write: rows [n,Hkv,d] -> planes [B][Hkv][N_cap][d] of the cache
+// dtype. Pure data movement (plus the cast): each thread moves 8 consecutive
+// elements of K and of V with 128-bit accesses; 16 threads cover a 256-byte
+// bf16 row on both sides.
+typedef unsigned int kvw_u32x4 __attribute__((ext_vector_type(4)));
+typedef float kvw_f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename S> struct Row8;
+template <> struct Row8<float> {
+  kvw_f32x4 lo, hi;
+  __device__ __forceinline__ void load(const float* p) { lo = *(const kvw_f32x4*)p; hi = *(const kvw_f32x4*)(p + 4); }
+  __device__ __forceinline__ float get(int i) const { return i < 4 ? lo[i] : hi[i - 4]; }
+};
+template <> struct Row8<bf16_t> {
+  kvw_u32x4 w;
+  __device__ __forceinline__ void load(const bf16_t* p) { w = *(const kvw_u32x4*)p; }
+  __device__ __forceinline__ float get(int i) const {
+    const unsigned x = w[i >> 1];
+    return __uint_as_float((i & 1) ? (x & 0xffff0000u) : (x << 16));
+  }
+};
+template <typename S>
+__device__ __forceinline__ void store8(float* p, const Row8<S>& r) {
+  kvw_f32x4 a = {r.get(0), r.get(1), r.get(2), r.get(3)}, b = {r.get(4), r.get(5), r.get(6), r.get(7)};
+  *(kvw_f32x4*)p = a;
+  *(kvw_f32x4*)(p + 4) = b;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const Row8<bf16_t>& r) { *(kvw_u32x4*)p = r.w; }   // same dtype: bit copy
+__device__ __forceinline__ void store8(bf16_t* p, const Row8<float>& r) {
+  kvw_u32x4 w;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = (unsigned)f32_to_bf16(r.get(2 * i)) | ((unsigned)f32_to_bf16(r.get(2 * i + 1)) << 16);
+  *(kvw_u32x4*)p = w;
+}
+
 template <typename S, typename D>
 __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S* __restrict__ k,
                                                        const S* __restrict__ v, int b, int64_t pos0, int64_t n) {
@@ -229,13 +263,11 @@ __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S*
     const int64_t r = idx / ((int64_t)d8 * c.Hkv);
     const int64_t src = (r * c.Hkv + g) * c.d + e8 * 8;
     const int64_t dst = (((int64_t)b * c.Hkv + g) * c.N_cap + pos0 + r) * c.d + e8 * 8;
-    D* kd = (D*)c.k + dst;
-    D* vd = (D*)c.v + dst;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      Elem<D>::store(kd + e, Elem<S>::load(k + src + e));
-      Elem<D>::store(vd + e, Elem<S>::load(v + src + e));
-    }
+    Row8<S> kr, vr;
+    kr.load(k + src);
+    vr.load(v + src);
+    store8((D*)c.k + dst, kr);
+    store8((D*)c.v + dst, vr);
   }
 }
 
@@ -243,7 +275,7 @@ hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v,
                            int src_dtype, hipStream_t s) {
   const int64_t total = n * c.Hkv * (c.d / 8);
   int64_t blocks = (total + 255) / 256;
-  if (blocks > 65536) blocks = 65536;
+  if (blocks > 16384) blocks = 16384;
   dim3 grid((unsigned)blocks), block(256);
   if (src_dtype == YOCO_F32 && c.dtype == YOCO_F32)
     hipLaunchKernelGGL((kv_write_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, n);

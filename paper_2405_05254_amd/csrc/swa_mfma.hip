@@ -22,10 +22,13 @@
 // the bf16 output, and the two together exceed a 2e-3 mean relative error.
 // |v| >= 65520 is outside this kernel's domain (it overflows fp16).
 //
-// K and V tiles are staged global -> registers -> LDS (double buffered, the
-// next tile's loads are in flight while the current one is computed). LDS
-// rows are 256 B; K is XOR-swizzled in 16-byte chunks and V in 32-byte chunks
-// so both operand read patterns are bank-conflict free.
+// Tiles are double buffered in LDS and the next tile is in flight while the
+// current one is computed: K by global_load_lds (no registers), V through
+// registers because of the conversion. LDS rows are 256 B; K is XOR-swizzled
+// in 16-byte chunks and V in 32-byte chunks so both operand read patterns are
+// bank-conflict free.
+#include <type_traits>
+
 #include "yoco_common.h"
 
 namespace yoco {
@@ -84,9 +87,13 @@ struct Args {
 };
 
 __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
-  __shared__ __attribute__((aligned(1024))) char smem[2][2][kTileBytes];   // [buffer][K, V]
+  // Two tile buffers as distinct arrays: the compiler then knows that a DMA
+  // into one buffer does not alias the operand reads of the other.
+  __shared__ __attribute__((aligned(1024))) char k_a[kTileBytes], k_b[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char v_a[kTileBytes], v_b[kTileBytes];
   const AttnView& a = g.a;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront-uniform: scalar branches below
   const int hf = lane >> 5, lq = lane & 31;
 
   // ---- workgroup -> (sequence, head, query tile). Workgroups are dealt to
@@ -116,26 +123,40 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const bf16_t* kg = (const bf16_t*)a.k + b * a.kv_stride_b + kvh * a.kv_stride_h;
   const bf16_t* vg = (const bf16_t*)a.v + b * a.kv_stride_b + kvh * a.kv_stride_h;
 
-  // ---- staging assignment: thread -> 16-byte chunk c16 of rows srow + 16 i
-  const int c16 = tid & 15, srow = tid >> 4;
-  u32x4 kst[4], vst[4];
-  auto load_tile = [&](int jt) {
+  // ---- tile staging. K goes global -> LDS directly (global_load_lds: lane l of
+  // a wave instruction fills LDS bytes [16 l, 16 l + 16) after the uniform base,
+  // so the XOR swizzle is applied to the global chunk each lane fetches). V goes
+  // through registers because it is converted to fp16 on the way.
+  const int c16 = tid & 15, srow = tid >> 4;             // thread -> 16-byte chunk c16 of rows srow + 16 i
+  const uint32_t row_bytes = (uint32_t)a.kv_stride_n * 2u;
+  u32x4 vst[4];
+  auto load_tile = [&](int jt, char* k_dst) {
+    const int64_t tile_row0 = (int64_t)jt * kBN;
+    const int lim = (int)(g.n_keys - 1 - tile_row0 < kBN - 1 ? g.n_keys - 1 - tile_row0 : kBN - 1);   // last row that exists
+    const char* kt = (const char*)(kg + tile_row0 * a.kv_stride_n);
+    const char* vt = (const char*)(vg + tile_row0 * a.kv_stride_n);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int64_t row = (int64_t)jt * kBN + srow + 16 * i;
-      row = row < g.n_keys ? row : g.n_keys - 1;        // clamped rows are masked below
-      kst[i] = *(const u32x4*)(kg + row * a.kv_stride_n + c16 * 8);
-      vst[i] = *(const u32x4*)(vg + row * a.kv_stride_n + c16 * 8);
+      const int lrow = wave * 16 + i * 4 + (lane >> 4);   // LDS row this lane fills
+      const int grow = lrow < lim ? lrow : lim;           // rows past the end repeat the last one (masked later)
+      const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(((lane & 15) ^ (lrow & 15)) << 4);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt + off),
+                                       (__attribute__((address_space(3))) void*)(k_dst + (wave * 16 + i * 4) * 256), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int lrow = srow + 16 * i;
+      const int grow = lrow < lim ? lrow : lim;
+      vst[i] = *(const u32x4*)(vt + ((uint32_t)grow * row_bytes + (uint32_t)(c16 << 4)));
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](char* v_dst) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = srow + 16 * i;
-      *(u32x4*)(&smem[buf][0][row * 256 + ((c16 ^ (row & 15)) << 4)]) = kst[i];
       u32x4 vh = {bf16x2_to_f16x2(vst[i][0]), bf16x2_to_f16x2(vst[i][1]), bf16x2_to_f16x2(vst[i][2]),
                   bf16x2_to_f16x2(vst[i][3])};
-      *(u32x4*)(&smem[buf][1][row * 256 + (((((c16 >> 1) ^ (row & 7)) << 1) | (c16 & 1)) << 4)]) = vh;
+      *(u32x4*)(v_dst + row * 256 + (((((c16 >> 1) ^ (row & 7)) << 1) | (c16 & 1)) << 4)) = vh;
     }
   };
 
@@ -150,16 +171,14 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qg + ks * 16 + hf * 8));
 
   // ---- per-lane LDS byte offsets of the operand fragments (within a tile)
-  // K (A operand of S^T): row mb*32 + lq, chunk (ks*2 + hf) ^ (row & 15)
-  int koff[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) koff[ks] = lq * 256 + ((((ks << 1) | hf) ^ (lq & 15)) << 4);
+  // K (A operand of S^T): row mb*32 + lq, chunk (ks*2 + hf) ^ (row & 15). The
+  // chunk field is bits 4..7 of the offset, so k-step ks is koff0 ^ (ks << 5).
+  const int koff0 = lq * 256 + ((hf ^ (lq & 15)) << 4);
   // V^T (A operand of O^T) via transposing reads: lane s = lane % 16 of a block
-  // of 16 supplies row z = hf*4 + s/4 (+ t*16 + half*8), dims (mb*2 + db)*16 + 4*(s%4)
+  // of 16 supplies row z = hf*4 + s/4 (+ t*16 + half*8), dims (mb*2 + db)*16 + 4*(s%4),
+  // 32-byte chunk (mb*2 + db) ^ z: dim block mb is voff0 ^ (mb << 6).
   const int s16 = lane & 15, db = (lane >> 4) & 1, z = hf * 4 + (s16 >> 2);
-  int voff[4];
-#pragma unroll
-  for (int mb = 0; mb < 4; ++mb) voff[mb] = z * 256 + ((((mb << 1) | db) ^ z) << 5) + ((s16 & 3) << 3);
+  const int voff0 = z * 256 + ((db ^ z) << 5) + ((s16 & 3) << 3);
 
   const float c = a.scale * kLog2e;                     // scores are kept raw; exponents use s * c
   const float lazy_raw = kLazyLog2 / c;
@@ -174,101 +193,132 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const int pq_rel0 = pw_lo + lq;                                        // this lane's query, same origin
   const int win32 = win > (1 << 30) ? (1 << 30) : (int)win;
 
-  load_tile(jt_lo);
-  store_tile(0);
+  load_tile(jt_lo, k_a);
+  store_tile(v_a);
   __syncthreads();
+  // Q is complete here; saying so keeps the loop free of waits on it (the
+  // tile prefetch loads issued inside the loop must stay in flight).
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
 
-  for (int jt = jt_lo; jt <= jt_hi; ++jt) {
-    const int buf = (jt - jt_lo) & 1;
-    if (jt < jt_hi) load_tile(jt + 1);
+  // One key tile for this wavefront. MASKED = false: every key of the tile is
+  // visible to every row of the wavefront (no mask, no branches).
+  auto compute = [&](auto masked_tag, char* k_buf, char* v_buf, const int j0r, const bool need0, const bool need1) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    lds_char* kb = (lds_char*)k_buf;
+    lds_char* vb = (lds_char*)v_buf;
+    int kbase = koff0, vbase = voff0;
+    asm volatile("" : "+v"(kbase), "+v"(vbase));      // keep the 12 derived offsets out of long-lived registers
+    auto kfrag = [&](int ks, int mb) {
+      return __builtin_bit_cast(bf16x8, *(const __attribute__((address_space(3))) u32x4*)(kb + (kbase ^ (ks << 5)) + mb * 32 * 256));
+    };
+    // ---- S^T = K Q^T, two independent accumulator chains (key halves)
+    f32x16 s0, s1;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (!MASKED || (need0 && need1)) {
+#pragma unroll
+      for (int kh = 0; kh < 4; ++kh) {
+        bf16x8 k0[2], k1[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) { k0[i] = kfrag(kh * 2 + i, 0); k1[i] = kfrag(kh * 2 + i, 1); }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s1, 0, 0, 0);
+        }
+      }
+    } else {
+      s0 = zero;
+      s1 = zero;
+      if (need0) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 0), qf[ks], s0, 0, 0, 0);
+      }
+      if (need1) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 1), qf[ks], s1, 0, 0, 0);
+      }
+    }
+    if (MASKED) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = j0r + (r >> 2) * 8 + hf * 4 + (r & 3);
+        s0[r] = (need0 && ((unsigned)(pq_rel0 - key) < (unsigned)win32)) ? s0[r] : -INFINITY;
+        s1[r] = (need1 && ((unsigned)(pq_rel0 - key - 32) < (unsigned)win32)) ? s1[r] : -INFINITY;
+      }
+    }
+    // ---- online softmax (a query is the lane pair l, l ^ 32)
+    float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+    mx = fmaxf(mx, other_half(mx));
+    const bool grow = mx > m_used + lazy_raw;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      const float m_new = grow ? mx : m_used;
+      const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * c);
+      m_used = m_new;
+      l_lane *= alpha;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[mb][r] *= alpha;
+    }
+    const float mc = m_used * c;
+    unsigned pk0[8], pk1[8];
+    float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -mc));
+      const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[r + 1], c, -mc));
+      const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -mc));
+      const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[r + 1], c, -mc));
+      ps0 += a0 + a1;
+      ps1 += b0 + b1;
+      pk0[r >> 1] = pack_f16(a0, a1);
+      pk1[r >> 1] = pack_f16(b0, b1);
+    }
+    l_lane += ps0 + ps1;
+    // ---- O^T += V^T P^T ; k-step t covers keys t*16 .. t*16+15 of the tile
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (MASKED && !((t >> 1) ? need1 : need0)) continue;
+      const unsigned* pk = (t >> 1) ? pk1 : pk0;
+      const int pb = (t & 1) * 4;
+      u32x4 pu = {pk[pb], pk[pb + 1], pk[pb + 2], pk[pb + 3]};
+      const f16x8 pf = __builtin_bit_cast(f16x8, pu);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16) * 256));
+        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16 + 8) * 256));
+        u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+        u32x4 vu = {a0[0], a0[1], a1[0], a1[1]};
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vu), pf, acc_o[mb], 0, 0, 0);
+      }
+    }
+  };
+
+  // One loop step = one key tile: prefetch the next tile into the other
+  // buffer, compute this one, publish the prefetched V, barrier.
+  auto phase = [&](int jt, char* k_cur, char* v_cur, char* k_nxt, char* v_nxt) {
+    const bool more = jt < jt_hi;
+    if (more) load_tile(jt + 1, k_nxt);
     const int j0r = (jt - jt_lo) * kBN;                 // tile's first key, relative origin
     // half tiles (32 keys) this wavefront needs: some row sees some key
-    bool need[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      const int k_lo = j0r + mb * 32, k_hi = k_lo + 31;
-      need[mb] = (k_lo <= pw_lo + kNQ - 1) && (k_hi > pw_lo - win32);
-    }
-    if (need[0] || need[1]) {
-      lds_char* kb = (lds_char*)&smem[buf][0][0];
-      lds_char* vb = (lds_char*)&smem[buf][1][0];
-      // ---- S^T = K Q^T
-      f32x16 acc_s[2];
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[mb][r] = 0.f;
-        if (need[mb]) {
-#pragma unroll
-          for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 kf = __builtin_bit_cast(bf16x8, *(const __attribute__((address_space(3))) u32x4*)(kb + koff[ks] + mb * 32 * 256));
-            acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[mb], 0, 0, 0);
-          }
-        }
-      }
-      // ---- mask: full visibility iff every key <= every row and inside every window
-      const bool full = (j0r + kBN - 1 <= pw_lo) && (j0r > pw_lo + kNQ - 1 - win32) && need[0] && need[1];
-      if (!full) {
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = j0r + mb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-            const bool ok = need[mb] && ((unsigned)(pq_rel0 - key) < (unsigned)win32);
-            acc_s[mb][r] = ok ? acc_s[mb][r] : -INFINITY;
-          }
-      }
-      // ---- online softmax (per query = per lane pair l, l^32)
-      float mx = acc_s[0][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc_s[0][r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[1][r]);
-      mx = fmaxf(mx, other_half(mx));
-      const bool grow = mx > m_used + lazy_raw;
-      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float m_new = grow ? mx : m_used;
-        const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * c);
-        m_used = m_new;
-        l_lane *= alpha;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[mb][r] *= alpha;
-      }
-      const float mc = m_used * c;
-      unsigned pk[2][8];
-      float psum = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          const float p0f = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][r], c, -mc));
-          const float p1f = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][r + 1], c, -mc));
-          psum += p0f + p1f;
-          pk[mb][r >> 1] = pack_f16(p0f, p1f);
-        }
-      l_lane += psum;
-      // ---- O^T += V^T P^T ; k-step t covers keys t*16 .. t*16+15 of the tile
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        if (need[t >> 1]) {
-          const int pb = (t & 1) * 4;
-          u32x4 pu = {pk[t >> 1][pb], pk[t >> 1][pb + 1], pk[t >> 1][pb + 2], pk[t >> 1][pb + 3]};
-          const f16x8 pf = __builtin_bit_cast(f16x8, pu);
-#pragma unroll
-          for (int mb = 0; mb < 4; ++mb) {
-            const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + voff[mb] + (t * 16) * 256));
-            const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + voff[mb] + (t * 16 + 8) * 256));
-            u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-            u32x4 vu = {a0[0], a0[1], a1[0], a1[1]};
-            acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vu), pf, acc_o[mb], 0, 0, 0);
-          }
-        }
-      }
-    }
-    if (jt < jt_hi) store_tile(buf ^ 1);
-    __syncthreads();
+    const bool need0 = (j0r <= pw_lo + kNQ - 1) && (j0r + 31 > pw_lo - win32);
+    const bool need1 = (j0r + 32 <= pw_lo + kNQ - 1) && (j0r + 63 > pw_lo - win32);
+    // full visibility: every key <= every row of the wavefront and inside every window
+    const bool full = (j0r + kBN - 1 <= pw_lo) && (j0r > pw_lo + kNQ - 1 - win32);
+    if (full)
+      compute(std::false_type{}, k_cur, v_cur, j0r, true, true);
+    else if (need0 || need1)
+      compute(std::true_type{}, k_cur, v_cur, j0r, need0, need1);
+    if (more) store_tile(v_nxt);
+    __syncthreads();                                     // also waits for the K DMA of the next tile
+  };
+  for (int jt = jt_lo; jt <= jt_hi; jt += 2) {
+    phase(jt, k_a, v_a, k_b, v_b);
+    if (jt + 1 > jt_hi) break;
+    phase(jt + 1, k_b, v_b, k_a, v_a);
   }
 
   // ---- normalise and store O (bf16, rounded once)

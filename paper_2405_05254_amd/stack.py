@@ -2,6 +2,11 @@
 Eq. 1-3, Fig. 2 and 3). Attention runs in libyoco; RMSNorm, the projections,
 SwiGLU and the classifier are plain torch ops on the GPU (the non-attention
 GEMMs are not part of the library).
+
+Precision: the attention operands (Q, K, V, the global cache, O) have the
+kernel dtype; the residual stream and the glue GEMMs run in `glue_dtype`
+(fp32 by default, with the weights' stored values), so the only bf16 roundings
+on the path are the ones at the attention boundary.
 """
 import math
 
@@ -16,6 +21,13 @@ def _rmsnorm(x, gain, eps):
     return y.to(x.dtype)
 
 
+def _rows(x, fn, chunk=16384):
+    """Apply a row-wise function in row chunks (bounds the FFN intermediates at long T)."""
+    if x.shape[0] <= chunk:
+        return fn(x)
+    return torch.cat([fn(x[i:i + chunk]) for i in range(0, x.shape[0], chunk)])
+
+
 def _swiglu(x, L):
     return (torch.nn.functional.silu(x @ L["W_G"]) * (x @ L["W_1"])) @ L["W_2"]
 
@@ -24,11 +36,12 @@ class YocoStack:
     """weights: the dict produced by the synthetic generator (numpy arrays);
     dtype: torch.float32 or torch.bfloat16."""
 
-    def __init__(self, weights, dtype, device="cuda"):
-        self.dtype, self.device = dtype, device
+    def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32):
+        self.dtype, self.device, self.glue = dtype, device, glue_dtype
+        self.capture = None          # dict layer-name -> (q, k, v, o) when set by a test
 
         def dev(a):
-            return torch.as_tensor(a).to(device=device, dtype=dtype)
+            return torch.as_tensor(a).to(device=device, dtype=glue_dtype)
 
         def layer(L):
             return {k: dev(v) for k, v in L.items()}
@@ -47,22 +60,25 @@ class YocoStack:
     def self_decoder(self, tokens):
         X = self.embed[tokens]
         T = X.shape[0]
-        for L in self.self_layers:
+        for n, L in enumerate(self.self_layers):
             xn = _rmsnorm(X, L["ln1"], self.eps)
-            q = (xn @ L["W_Q"]).view(1, T, self.Hq, self.d)
-            k = (xn @ L["W_K"]).view(1, T, self.Hkv_self, self.d)
-            v = (xn @ L["W_V"]).view(1, T, self.Hkv_self, self.d)
-            a = yb.swa_prefill(q, k, v, self.window, self.scale).view(T, self.Hq * self.d)
-            Y = a @ L["W_O"] + X
-            X = _swiglu(_rmsnorm(Y, L["ln2"], self.eps), L) + Y
+            q = (xn @ L["W_Q"]).to(self.dtype).view(1, T, self.Hq, self.d)
+            k = (xn @ L["W_K"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
+            v = (xn @ L["W_V"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
+            o = yb.swa_prefill(q, k, v, self.window, self.scale)
+            if self.capture is not None and ("self%d" % n) in self.capture:
+                self.capture["self%d" % n] = (q[0], k[0], v[0], o[0])
+            Y = o.view(T, self.Hq * self.d).to(self.glue) @ L["W_O"] + X
+            del q, k, v, o, xn
+            X = _rows(Y, lambda y: _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y)
         return X
 
     # -- Eq. 2: the global cache, written once
     def write_cache(self, X, cache=None, pos0=0):
         T = X.shape[0]
         xn = _rmsnorm(X, self.kv["ln"], self.eps)
-        k = (xn @ self.kv["W_K"]).view(T, self.Hkv, self.d)
-        v = (xn @ self.kv["W_V"]).view(T, self.Hkv, self.d)
+        k = (xn @ self.kv["W_K"]).to(self.dtype).view(T, self.Hkv, self.d)
+        v = (xn @ self.kv["W_V"]).to(self.dtype).view(T, self.Hkv, self.d)
         if cache is None:
             cache = yb.KVCache(1, self.Hkv, self.d, T, self.dtype, self.device)
         yb.global_kv_write(cache, k, v, 0, pos0)
@@ -71,14 +87,20 @@ class YocoStack:
     # -- cross-decoder: Eq. 3
     def _cross_layer(self, X, L, attn):
         Tq = X.shape[0]
-        q = (_rmsnorm(X, L["ln1"], self.eps) @ L["W_Q"]).view(Tq, self.Hq, self.d)
-        a = attn(q).view(Tq, self.Hq * self.d)
+        q = (_rmsnorm(X, L["ln1"], self.eps) @ L["W_Q"]).to(self.dtype).view(Tq, self.Hq, self.d)
+        a = attn(q).view(Tq, self.Hq * self.d).to(self.glue)
         Y = a @ L["W_O"] + X
-        return _swiglu(_rmsnorm(Y, L["ln2"], self.eps), L) + Y
+        del q, a
+        return _rows(Y, lambda y: _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y)
 
     def cross_decoder_rows(self, X, cache, q_pos0):
-        for L in self.cross_layers:
-            X = self._cross_layer(X, L, lambda q: yb.cross_attn_prefill(cache, q, 0, q_pos0, self.scale))
+        for n, L in enumerate(self.cross_layers):
+            def attn(q, n=n):
+                o = yb.cross_attn_prefill(cache, q, 0, q_pos0, self.scale)
+                if self.capture is not None and ("cross%d" % n) in self.capture:
+                    self.capture["cross%d" % n] = (q, o)
+                return o
+            X = self._cross_layer(X, L, attn)
         return X
 
     def cross_decoder_decode(self, x_last, cache, length):

@@ -95,6 +95,38 @@ def stack_weights(seed, s, dtype):
     return w
 
 
+def stack_weights_device(seed, s, torch_dtype, device):
+    """The same random-init stack drawn on the device (the 1.4B-parameter
+    end-to-end configuration): N(0, 0.02) rounded to `torch_dtype`, gains 1."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    dm, Hq, d, ffn = s["d_model"], s["Hq"], s["d"], s["ffn"]
+
+    def mat(*shape):
+        x = torch.empty(shape, dtype=torch.float32, device=device)
+        x.normal_(0.0, 0.02, generator=g)
+        return x.to(torch_dtype)
+
+    def ones():
+        return torch.ones(dm, dtype=torch.float32, device=device)
+
+    def ffn_w():
+        return dict(ln2=ones(), W_G=mat(dm, ffn), W_1=mat(dm, ffn), W_2=mat(ffn, dm))
+
+    w = dict(Hq=Hq, Hkv_self=s["Hkv_self"], Hkv=s["Hkv"], d=d, window=s["window"], eps=s["eps"])
+    w["embed"] = mat(s["vocab"], dm)
+    w["self"] = [dict(ln1=ones(), W_Q=mat(dm, Hq * d), W_K=mat(dm, s["Hkv_self"] * d),
+                      W_V=mat(dm, s["Hkv_self"] * d), W_O=mat(Hq * d, dm), **ffn_w())
+                 for _ in range(s["n_self"])]
+    w["kv"] = dict(ln=ones(), W_K=mat(dm, s["Hkv"] * d), W_V=mat(dm, s["Hkv"] * d))
+    w["cross"] = [dict(ln1=ones(), W_Q=mat(dm, Hq * d), W_O=mat(Hq * d, dm), **ffn_w())
+                  for _ in range(s["n_cross"])]
+    w["final_ln"] = ones()
+    w["W_out"] = mat(dm, s["vocab"])
+    return w
+
+
 def tokens(seed, T, vocab):
     return np.random.default_rng(seed + 7919).integers(0, vocab, size=T, dtype=np.int64)
 
