@@ -19,7 +19,8 @@ class _Cache(C.Structure):
 
 
 def lib_path():
-    return os.path.join(_PKG, "libyoco.so")
+    """In-tree libyoco.so; YOCO_LIB_PATH names another build of the same library (development aid)."""
+    return os.environ.get("YOCO_LIB_PATH") or os.path.join(_PKG, "libyoco.so")
 
 
 def lib():

@@ -10,6 +10,7 @@ LIB = os.path.join(PKG, "libyoco.so")
 SOURCES = ["yoco_api.hip", "attn_generic.hip", "swa_mfma.hip", "decode_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
+         "-fno-honor-nans",        # fmax without NaN canonicalisation; -inf (the mask value) is still honoured
          "-Wno-unused-command-line-argument",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

@@ -5,8 +5,8 @@
 //
 // Workgroup = 4 wavefronts, 128 query rows of one head; wavefront w owns rows
 // 32w .. 32w+31. Keys are walked in tiles of 64, only tiles that intersect
-// some row's window are visited, and a wavefront skips the 32-key half tiles
-// that none of its own rows can see.
+// some row's window are visited, and a wavefront skips the tiles that none of
+// its own rows can see; the mask is applied only on the tiles that need it.
 //
 // Orientation: S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_32x32x16_bf16, so
 // a query is a lane column (lane % 32) and keys / head dims run along the
@@ -22,9 +22,8 @@
 // the bf16 output, and the two together exceed a 2e-3 mean relative error.
 // |v| >= 65520 is outside this kernel's domain (it overflows fp16).
 //
-// Tiles are double buffered in LDS and the next tile is in flight while the
-// current one is computed: K by global_load_lds (no registers), V through
-// registers because of the conversion. LDS rows are 256 B; K is XOR-swizzled
+// Tiles are double buffered in LDS and the next tile is in flight (global ->
+// registers) while the current one is computed. LDS rows are 256 B; K is XOR-swizzled
 // in 16-byte chunks and V in 32-byte chunks so both operand read patterns are
 // bank-conflict free.
 #include <type_traits>
@@ -87,8 +86,8 @@ struct Args {
 };
 
 __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
-  // Two tile buffers as distinct arrays: the compiler then knows that a DMA
-  // into one buffer does not alias the operand reads of the other.
+  // Two tile buffers as distinct arrays, so that the compiler can tell the
+  // stores of the next tile from the operand reads of the current one.
   __shared__ __attribute__((aligned(1024))) char k_a[kTileBytes], k_b[kTileBytes];
   __shared__ __attribute__((aligned(1024))) char v_a[kTileBytes], v_b[kTileBytes];
   const AttnView& a = g.a;
@@ -123,39 +122,34 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const bf16_t* kg = (const bf16_t*)a.k + b * a.kv_stride_b + kvh * a.kv_stride_h;
   const bf16_t* vg = (const bf16_t*)a.v + b * a.kv_stride_b + kvh * a.kv_stride_h;
 
-  // ---- tile staging. K goes global -> LDS directly (global_load_lds: lane l of
-  // a wave instruction fills LDS bytes [16 l, 16 l + 16) after the uniform base,
-  // so the XOR swizzle is applied to the global chunk each lane fetches). V goes
-  // through registers because it is converted to fp16 on the way.
+  // ---- tile staging: global -> registers -> LDS for both K and V. (LDS-direct
+  // loads were measured slower here: a wavefront's later LDS reads queue behind
+  // its pending global_load_lds, which exposes one memory latency per tile.)
+  // V is converted to fp16 on the way.
   const int c16 = tid & 15, srow = tid >> 4;             // thread -> 16-byte chunk c16 of rows srow + 16 i
   const uint32_t row_bytes = (uint32_t)a.kv_stride_n * 2u;
-  u32x4 vst[4];
-  auto load_tile = [&](int jt, char* k_dst) {
+  u32x4 kst[4], vst[4];
+  auto load_tile = [&](int jt) {
     const int64_t tile_row0 = (int64_t)jt * kBN;
     const int lim = (int)(g.n_keys - 1 - tile_row0 < kBN - 1 ? g.n_keys - 1 - tile_row0 : kBN - 1);   // last row that exists
     const char* kt = (const char*)(kg + tile_row0 * a.kv_stride_n);
     const char* vt = (const char*)(vg + tile_row0 * a.kv_stride_n);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int lrow = wave * 16 + i * 4 + (lane >> 4);   // LDS row this lane fills
-      const int grow = lrow < lim ? lrow : lim;           // rows past the end repeat the last one (masked later)
-      const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(((lane & 15) ^ (lrow & 15)) << 4);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt + off),
-                                       (__attribute__((address_space(3))) void*)(k_dst + (wave * 16 + i * 4) * 256), 16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
       const int lrow = srow + 16 * i;
-      const int grow = lrow < lim ? lrow : lim;
-      vst[i] = *(const u32x4*)(vt + ((uint32_t)grow * row_bytes + (uint32_t)(c16 << 4)));
+      const int grow = lrow < lim ? lrow : lim;           // rows past the end repeat the last one (masked later)
+      const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(c16 << 4);
+      kst[i] = *(const u32x4*)(kt + off);
+      vst[i] = *(const u32x4*)(vt + off);
     }
   };
-  auto store_tile = [&](char* v_dst) {
+  auto store_tile = [&](char* k_dst, char* v_dst) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = srow + 16 * i;
       u32x4 vh = {bf16x2_to_f16x2(vst[i][0]), bf16x2_to_f16x2(vst[i][1]), bf16x2_to_f16x2(vst[i][2]),
                   bf16x2_to_f16x2(vst[i][3])};
+      *(u32x4*)(k_dst + row * 256 + ((c16 ^ (row & 15)) << 4)) = kst[i];
       *(u32x4*)(v_dst + row * 256 + (((((c16 >> 1) ^ (row & 7)) << 1) | (c16 & 1)) << 4)) = vh;
     }
   };
@@ -193,8 +187,8 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const int pq_rel0 = pw_lo + lq;                                        // this lane's query, same origin
   const int win32 = win > (1 << 30) ? (1 << 30) : (int)win;
 
-  load_tile(jt_lo, k_a);
-  store_tile(v_a);
+  load_tile(jt_lo);
+  store_tile(k_a, v_a);
   __syncthreads();
   // Q is complete here; saying so keeps the loop free of waits on it (the
   // tile prefetch loads issued inside the loop must stay in flight).
@@ -203,8 +197,9 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
 
   // One key tile for this wavefront. MASKED = false: every key of the tile is
   // visible to every row of the wavefront (no mask, no branches).
-  auto compute = [&](auto masked_tag, char* k_buf, char* v_buf, const int j0r, const bool need0, const bool need1) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
+  // One key tile for this wavefront. masked = false: every key of the tile is
+  // visible to every row of the wavefront and the mask block is skipped.
+  auto compute = [&](char* k_buf, char* v_buf, const int j0r, const bool masked) {
     lds_char* kb = (lds_char*)k_buf;
     lds_char* vb = (lds_char*)v_buf;
     int kbase = koff0, vbase = voff0;
@@ -215,36 +210,23 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
     // ---- S^T = K Q^T, two independent accumulator chains (key halves)
     f32x16 s0, s1;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (!MASKED || (need0 && need1)) {
 #pragma unroll
-      for (int kh = 0; kh < 4; ++kh) {
-        bf16x8 k0[2], k1[2];
+    for (int kh = 0; kh < 4; ++kh) {
+      bf16x8 k0[2], k1[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) { k0[i] = kfrag(kh * 2 + i, 0); k1[i] = kfrag(kh * 2 + i, 1); }
+      for (int i = 0; i < 2; ++i) { k0[i] = kfrag(kh * 2 + i, 0); k1[i] = kfrag(kh * 2 + i, 1); }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s1, 0, 0, 0);
-        }
-      }
-    } else {
-      s0 = zero;
-      s1 = zero;
-      if (need0) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 0), qf[ks], s0, 0, 0, 0);
-      }
-      if (need1) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 1), qf[ks], s1, 0, 0, 0);
+      for (int i = 0; i < 2; ++i) {
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s1, 0, 0, 0);
       }
     }
-    if (MASKED) {
+    if (masked) {                                       // keys outside (p - C, p] of this lane's query
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = j0r + (r >> 2) * 8 + hf * 4 + (r & 3);
-        s0[r] = (need0 && ((unsigned)(pq_rel0 - key) < (unsigned)win32)) ? s0[r] : -INFINITY;
-        s1[r] = (need1 && ((unsigned)(pq_rel0 - key - 32) < (unsigned)win32)) ? s1[r] : -INFINITY;
+        s0[r] = ((unsigned)(pq_rel0 - key) < (unsigned)win32) ? s0[r] : -INFINITY;
+        s1[r] = ((unsigned)(pq_rel0 - key - 32) < (unsigned)win32) ? s1[r] : -INFINITY;
       }
     }
     // ---- online softmax (a query is the lane pair l, l ^ 32)
@@ -265,23 +247,18 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
     }
     const float mc = m_used * c;
     unsigned pk0[8], pk1[8];
-    float ps0 = 0.f, ps1 = 0.f;
+    const unsigned ones = 0x3c003c00u;                  // (1.0, 1.0) in fp16
 #pragma unroll
     for (int r = 0; r < 16; r += 2) {
-      const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -mc));
-      const float a1 = __builtin_amdgcn_exp2f(fmaf(s0[r + 1], c, -mc));
-      const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -mc));
-      const float b1 = __builtin_amdgcn_exp2f(fmaf(s1[r + 1], c, -mc));
-      ps0 += a0 + a1;
-      ps1 += b0 + b1;
-      pk0[r >> 1] = pack_f16(a0, a1);
-      pk1[r >> 1] = pack_f16(b0, b1);
+      pk0[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s0[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s0[r + 1], c, -mc)));
+      pk1[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s1[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s1[r + 1], c, -mc)));
+      // the row sum uses the rounded weights, the ones the second product sees
+      l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk0[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
+      l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk1[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
     }
-    l_lane += ps0 + ps1;
     // ---- O^T += V^T P^T ; k-step t covers keys t*16 .. t*16+15 of the tile
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (MASKED && !((t >> 1) ? need1 : need0)) continue;
       const unsigned* pk = (t >> 1) ? pk1 : pk0;
       const int pb = (t & 1) * 4;
       u32x4 pu = {pk[pb], pk[pb + 1], pk[pb + 2], pk[pb + 3]};
@@ -301,19 +278,15 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   // buffer, compute this one, publish the prefetched V, barrier.
   auto phase = [&](int jt, char* k_cur, char* v_cur, char* k_nxt, char* v_nxt) {
     const bool more = jt < jt_hi;
-    if (more) load_tile(jt + 1, k_nxt);
+    if (more) load_tile(jt + 1);
     const int j0r = (jt - jt_lo) * kBN;                 // tile's first key, relative origin
-    // half tiles (32 keys) this wavefront needs: some row sees some key
-    const bool need0 = (j0r <= pw_lo + kNQ - 1) && (j0r + 31 > pw_lo - win32);
-    const bool need1 = (j0r + 32 <= pw_lo + kNQ - 1) && (j0r + 63 > pw_lo - win32);
+    // does some row of this wavefront see some key of the tile?
+    const bool need = (j0r <= pw_lo + kNQ - 1) && (j0r + kBN - 1 > pw_lo - win32);
     // full visibility: every key <= every row of the wavefront and inside every window
     const bool full = (j0r + kBN - 1 <= pw_lo) && (j0r > pw_lo + kNQ - 1 - win32);
-    if (full)
-      compute(std::false_type{}, k_cur, v_cur, j0r, true, true);
-    else if (need0 || need1)
-      compute(std::true_type{}, k_cur, v_cur, j0r, need0, need1);
-    if (more) store_tile(v_nxt);
-    __syncthreads();                                     // also waits for the K DMA of the next tile
+    if (need) compute(k_cur, v_cur, j0r, !full);
+    if (more) store_tile(k_nxt, v_nxt);
+    __syncthreads();
   };
   for (int jt = jt_lo; jt <= jt_hi; jt += 2) {
     phase(jt, k_a, v_a, k_b, v_b);
