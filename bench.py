@@ -37,8 +37,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-decode", action="store_true", help="skip the two decode workloads")
-    ap.add_argument("--only", choices=["all", "swa", "decode"], default="all",
-                    help="profiling aid: 'swa' runs only the SWA prefill launches, 'decode' only the decode workloads")
+    ap.add_argument("--only", choices=["all", "swa", "decode", "calib"], default="all",
+                    help="profiling aid: 'swa' runs only the SWA prefill launches, 'decode' only the decode workloads, "
+                         "'calib' only a 1 GiB device-to-device copy (the known-size kernel the HBM byte counters are scaled by)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -55,6 +56,14 @@ def main():
     yoco.lib()                                   # no library, no benchmark: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda"
+    if args.only == "calib":
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib": "3 device-to-device copies of 1 GiB (reads 2^30 B, writes 2^30 B each)"}))
+        return
     c = ys.CONFIGS["swa_prefill_32k"]
     T, H, d, C = c["T"], c["Hq"], c["d"], c["window"]
     Hkv_cache = ys.CONFIGS["decode_b16_32k"]["Hkv"]

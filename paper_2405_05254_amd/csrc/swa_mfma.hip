@@ -122,36 +122,45 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const bf16_t* kg = (const bf16_t*)a.k + b * a.kv_stride_b + kvh * a.kv_stride_h;
   const bf16_t* vg = (const bf16_t*)a.v + b * a.kv_stride_b + kvh * a.kv_stride_h;
 
+  // ---- tile walk. The n_t tiles of this workgroup are visited in the cyclic
+  // order "tile index mod n_t" (any order is valid for an online softmax):
+  // neighbouring query tiles, which share all but two of their key tiles and
+  // run at the same time on the same XCD, then touch the same key tile at the
+  // same step, so a tile comes from HBM once and from L2 for its other readers.
+  const int n_t = jt_hi - jt_lo + 1;
+  const int rot = n_t - jt_lo % n_t;                      // step s visits tile jt_lo + (s + rot) % n_t
+  auto tile_of = [&](int s) { return jt_lo + (s + rot) % n_t; };
+
   // ---- tile staging: global -> registers -> LDS for both K and V. (LDS-direct
   // loads were measured slower here: a wavefront's later LDS reads queue behind
   // its pending global_load_lds, which exposes one memory latency per tile.)
-  // V is converted to fp16 on the way.
+  // V is converted to fp16 on the way. The rows of step s+1 are published
+  // during the first product of step s, and the loads of step s+2 follow them.
   const int c16 = tid & 15, srow = tid >> 4;             // thread -> 16-byte chunk c16 of rows srow + 16 i
   const uint32_t row_bytes = (uint32_t)a.kv_stride_n * 2u;
+  // LDS byte offsets of row srow (row srow + 16 i is 4096 i further: the
+  // swizzles depend on row & 15 / row & 7 only, which 16 i does not change)
+  const int kst_off = srow * 256 + ((c16 ^ (srow & 15)) << 4);
+  const int vst_off = srow * 256 + (((((c16 >> 1) ^ (srow & 7)) << 1) | (c16 & 1)) << 4);
   u32x4 kst[4], vst[4];
-  auto load_tile = [&](int jt) {
+  auto load_row = [&](int jt, int i) {
     const int64_t tile_row0 = (int64_t)jt * kBN;
     const int lim = (int)(g.n_keys - 1 - tile_row0 < kBN - 1 ? g.n_keys - 1 - tile_row0 : kBN - 1);   // last row that exists
-    const char* kt = (const char*)(kg + tile_row0 * a.kv_stride_n);
-    const char* vt = (const char*)(vg + tile_row0 * a.kv_stride_n);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int lrow = srow + 16 * i;
-      const int grow = lrow < lim ? lrow : lim;           // rows past the end repeat the last one (masked later)
-      const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(c16 << 4);
-      kst[i] = *(const u32x4*)(kt + off);
-      vst[i] = *(const u32x4*)(vt + off);
-    }
+    const int lrow = srow + 16 * i;
+    const int grow = lrow < lim ? lrow : lim;             // rows past the end repeat the last one (masked later)
+    const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(c16 << 4);
+    kst[i] = *(const u32x4*)((const char*)(kg + tile_row0 * a.kv_stride_n) + off);
+    vst[i] = *(const u32x4*)((const char*)(vg + tile_row0 * a.kv_stride_n) + off);
   };
-  auto store_tile = [&](char* k_dst, char* v_dst) {
+  auto load_tile = [&](int jt) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = srow + 16 * i;
-      u32x4 vh = {bf16x2_to_f16x2(vst[i][0]), bf16x2_to_f16x2(vst[i][1]), bf16x2_to_f16x2(vst[i][2]),
-                  bf16x2_to_f16x2(vst[i][3])};
-      *(u32x4*)(k_dst + row * 256 + ((c16 ^ (row & 15)) << 4)) = kst[i];
-      *(u32x4*)(v_dst + row * 256 + (((((c16 >> 1) ^ (row & 7)) << 1) | (c16 & 1)) << 4)) = vh;
-    }
+    for (int i = 0; i < 4; ++i) load_row(jt, i);
+  };
+  auto store_row = [&](char* k_dst, char* v_dst, int i) {
+    u32x4 vh = {bf16x2_to_f16x2(vst[i][0]), bf16x2_to_f16x2(vst[i][1]), bf16x2_to_f16x2(vst[i][2]),
+                bf16x2_to_f16x2(vst[i][3])};
+    *(u32x4*)(k_dst + kst_off + i * 4096) = kst[i];
+    *(u32x4*)(v_dst + vst_off + i * 4096) = vh;
   };
 
   // ---- Q^T fragments (B operand): lane holds query lq, dims ks*16 + hf*8 .. +8
@@ -187,111 +196,137 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   const int pq_rel0 = pw_lo + lq;                                        // this lane's query, same origin
   const int win32 = win > (1 << 30) ? (1 << 30) : (int)win;
 
-  load_tile(jt_lo);
-  store_tile(k_a, v_a);
+  // ---- prologue: tile of step 0 into buffer a, tile of step 1 in flight
+  load_tile(tile_of(0));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) store_row(k_a, v_a, i);
+  if (n_t > 1) load_tile(tile_of(1));
   __syncthreads();
   // Q is complete here; saying so keeps the loop free of waits on it (the
   // tile prefetch loads issued inside the loop must stay in flight).
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
 
-  // One key tile for this wavefront. MASKED = false: every key of the tile is
-  // visible to every row of the wavefront (no mask, no branches).
-  // One key tile for this wavefront. masked = false: every key of the tile is
-  // visible to every row of the wavefront and the mask block is skipped.
-  auto compute = [&](char* k_buf, char* v_buf, const int j0r, const bool masked) {
-    lds_char* kb = (lds_char*)k_buf;
-    lds_char* vb = (lds_char*)v_buf;
+  // ---- one step = one key tile (64 keys) for this wavefront:
+  //   [S^T = K Q^T  with  publishing the staged rows of the next step's tile
+  //    and issuing the loads of the tile after it]
+  //   mask (edge tiles only), running max, lazy rescale
+  //   [weights and O^T += V^T P^T]
+  // The first and third part each mix MFMA with vector work in one basic block,
+  // so the two wavefronts that share a SIMD (one per resident workgroup) can
+  // overlap their pipes in most phase combinations.
+  auto step = [&](int st, char* k_cur, char* v_cur, char* k_nxt, char* v_nxt) {
+    const int jt = tile_of(st);
+    const int j0r = (jt - jt_lo) * kBN;                 // tile's first key, relative origin
+    // does some row of this wavefront see some key of the tile? / every row every key?
+    const bool need = (j0r <= pw_lo + kNQ - 1) && (j0r + kBN - 1 > pw_lo - win32);
+    const bool full = (j0r + kBN - 1 <= pw_lo) && (j0r > pw_lo + kNQ - 1 - win32);
+    // the same for the two 32-key halves: on edge tiles a wavefront multiplies only the halves it needs
+    const bool need0 = need && (j0r + 31 > pw_lo - win32);
+    const bool need1 = need && (j0r + 32 <= pw_lo + kNQ - 1);
+    const bool both = need0 && need1;
+    const bool stage = st + 1 < n_t, prefetch = st + 2 < n_t;
+    lds_char* kb = (lds_char*)k_cur;
+    lds_char* vb = (lds_char*)v_cur;
     int kbase = koff0, vbase = voff0;
-    asm volatile("" : "+v"(kbase), "+v"(vbase));      // keep the 12 derived offsets out of long-lived registers
+    asm volatile("" : "+v"(kbase), "+v"(vbase));        // keep the 12 derived offsets out of long-lived registers
     auto kfrag = [&](int ks, int mb) {
       return __builtin_bit_cast(bf16x8, *(const __attribute__((address_space(3))) u32x4*)(kb + (kbase ^ (ks << 5)) + mb * 32 * 256));
     };
-    // ---- S^T = K Q^T, two independent accumulator chains (key halves)
-    f32x16 s0, s1;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 s0 = zero, s1 = zero;                         // keys 0..31 and 32..63 of the tile
+    if (both && prefetch) {
+      // the common case, one basic block: 16 MFMAs, the 4 staged rows, 8 loads
+      const int jt2 = tile_of(st + 2);
 #pragma unroll
-    for (int kh = 0; kh < 4; ++kh) {
-      bf16x8 k0[2], k1[2];
+      for (int kh = 0; kh < 4; ++kh) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) { k0[i] = kfrag(kh * 2 + i, 0); k1[i] = kfrag(kh * 2 + i, 1); }
+        for (int i = 0; i < 2; ++i) {
+          const int ks = kh * 2 + i;
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 0), qf[ks], ks == 0 ? zero : s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 1), qf[ks], ks == 0 ? zero : s1, 0, 0, 0);
+        }
+        // a staged row is published and its registers reloaded at once: the
+        // loads go out one pair at a time between the products, not as a burst
+        store_row(k_nxt, v_nxt, kh);
+        load_row(jt2, kh);
+      }
+    } else {
+      if (need0) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1[i], qf[kh * 2 + i], (kh == 0 && i == 0) ? zero : s1, 0, 0, 0);
+        for (int ks = 0; ks < 8; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 0), qf[ks], ks == 0 ? zero : s0, 0, 0, 0);
+      }
+      if (need1) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 1), qf[ks], ks == 0 ? zero : s1, 0, 0, 0);
+      }
+      if (stage) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) store_row(k_nxt, v_nxt, i);
+      }
+      if (prefetch) load_tile(tile_of(st + 2));
+    }
+    if (need) {
+      if (!full) {                                       // keys outside (p - C, p] of this lane's query
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0r + (r >> 2) * 8 + hf * 4 + (r & 3);
+          s0[r] = (need0 && (unsigned)(pq_rel0 - key) < (unsigned)win32) ? s0[r] : -INFINITY;
+          s1[r] = (need1 && (unsigned)(pq_rel0 - key - 32) < (unsigned)win32) ? s1[r] : -INFINITY;
+        }
+      }
+      // ---- online softmax (a query is the lane pair l, l ^ 32); the
+      // accumulators are rescaled only when the max grows by more than 2^kLazyLog2
+      float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+      mx = fmaxf(mx, other_half(mx));
+      const bool grow = mx > m_used + lazy_raw;
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float m_new = grow ? mx : m_used;
+        const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * c);
+        m_used = m_new;
+        l_lane *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[mb][r] *= alpha;
+      }
+      const float mc = m_used * c;
+      unsigned pk0[8], pk1[8];
+      const unsigned ones = 0x3c003c00u;                // (1.0, 1.0) in fp16
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        pk0[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s0[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s0[r + 1], c, -mc)));
+        pk1[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s1[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s1[r + 1], c, -mc)));
+        // the row sum uses the rounded weights, the ones the second product sees
+        l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk0[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
+        l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk1[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
+      }
+      // ---- O^T += V^T P^T ; k-step t covers keys t*16 .. t*16+15 of the tile
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (!both && !((t >> 1) ? need1 : need0)) continue;   // a skipped half has zero weights
+        const unsigned* pk = (t >> 1) ? pk1 : pk0;
+        const int pb = (t & 1) * 4;
+        u32x4 pu = {pk[pb], pk[pb + 1], pk[pb + 2], pk[pb + 3]};
+        const f16x8 pf = __builtin_bit_cast(f16x8, pu);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16) * 256));
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16 + 8) * 256));
+          u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+          u32x4 vu = {a0[0], a0[1], a1[0], a1[1]};
+          acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vu), pf, acc_o[mb], 0, 0, 0);
+        }
       }
     }
-    if (masked) {                                       // keys outside (p - C, p] of this lane's query
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = j0r + (r >> 2) * 8 + hf * 4 + (r & 3);
-        s0[r] = ((unsigned)(pq_rel0 - key) < (unsigned)win32) ? s0[r] : -INFINITY;
-        s1[r] = ((unsigned)(pq_rel0 - key - 32) < (unsigned)win32) ? s1[r] : -INFINITY;
-      }
-    }
-    // ---- online softmax (a query is the lane pair l, l ^ 32)
-    float mx = fmaxf(s0[0], s1[0]);
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
-    mx = fmaxf(mx, other_half(mx));
-    const bool grow = mx > m_used + lazy_raw;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-      const float m_new = grow ? mx : m_used;
-      const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * c);
-      m_used = m_new;
-      l_lane *= alpha;
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[mb][r] *= alpha;
-    }
-    const float mc = m_used * c;
-    unsigned pk0[8], pk1[8];
-    const unsigned ones = 0x3c003c00u;                  // (1.0, 1.0) in fp16
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      pk0[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s0[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s0[r + 1], c, -mc)));
-      pk1[r >> 1] = pack_f16(__builtin_amdgcn_exp2f(fmaf(s1[r], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s1[r + 1], c, -mc)));
-      // the row sum uses the rounded weights, the ones the second product sees
-      l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk0[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
-      l_lane = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pk1[r >> 1]), __builtin_bit_cast(f16x2, ones), l_lane, false);
-    }
-    // ---- O^T += V^T P^T ; k-step t covers keys t*16 .. t*16+15 of the tile
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const unsigned* pk = (t >> 1) ? pk1 : pk0;
-      const int pb = (t & 1) * 4;
-      u32x4 pu = {pk[pb], pk[pb + 1], pk[pb + 2], pk[pb + 3]};
-      const f16x8 pf = __builtin_bit_cast(f16x8, pu);
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
-        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16) * 256));
-        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + (vbase ^ (mb << 6)) + (t * 16 + 8) * 256));
-        u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
-        u32x4 vu = {a0[0], a0[1], a1[0], a1[1]};
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vu), pf, acc_o[mb], 0, 0, 0);
-      }
-    }
-  };
-
-  // One loop step = one key tile: prefetch the next tile into the other
-  // buffer, compute this one, publish the prefetched V, barrier.
-  auto phase = [&](int jt, char* k_cur, char* v_cur, char* k_nxt, char* v_nxt) {
-    const bool more = jt < jt_hi;
-    if (more) load_tile(jt + 1);
-    const int j0r = (jt - jt_lo) * kBN;                 // tile's first key, relative origin
-    // does some row of this wavefront see some key of the tile?
-    const bool need = (j0r <= pw_lo + kNQ - 1) && (j0r + kBN - 1 > pw_lo - win32);
-    // full visibility: every key <= every row of the wavefront and inside every window
-    const bool full = (j0r + kBN - 1 <= pw_lo) && (j0r > pw_lo + kNQ - 1 - win32);
-    if (need) compute(k_cur, v_cur, j0r, !full);
-    if (more) store_tile(k_nxt, v_nxt);
     __syncthreads();
   };
-  for (int jt = jt_lo; jt <= jt_hi; jt += 2) {
-    phase(jt, k_a, v_a, k_b, v_b);
-    if (jt + 1 > jt_hi) break;
-    phase(jt + 1, k_b, v_b, k_a, v_a);
+  for (int st = 0; st < n_t; st += 2) {
+    step(st, k_a, v_a, k_b, v_b);
+    if (st + 1 >= n_t) break;
+    step(st + 1, k_b, v_b, k_a, v_a);
   }
 
   // ---- normalise and store O (bf16, rounded once)
