@@ -34,8 +34,8 @@ def swa_flops(T, H, d, C):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true", help="skip the two decode workloads")
     ap.add_argument("--only", choices=["all", "swa", "decode", "calib"], default="all",
                     help="profiling aid: 'swa' runs only the SWA prefill launches, 'decode' only the decode workloads, "
@@ -99,7 +99,7 @@ def main():
         if args.only == "swa":
             return
         yoco.global_kv_write(cache, khat, vhat, 0, 0)
-        yoco.cross_attn_prefill(cache, q_last, 0, T - 1, scale, out=o_last)
+        yoco.cross_attn_prefill(cache, q_last, 0, T - 1, scale, out=o_last, workspace=ws)
         yoco.cross_attn_decode(cache, q_last, lens, scale, ws, out=o_dec)
 
     for _ in range(args.warmup):
@@ -132,7 +132,7 @@ def main():
             ln = torch.full((B,), N, dtype=torch.int64, device=dev)
             nb, splits = yoco.cross_attn_decode_workspace(kvc, Hq)
             w = torch.empty(nb, dtype=torch.uint8, device=dev)
-            reps = max(3, args.steps // 2)
+            reps = max(3, min(20, args.steps // 2))
             times = []
             for rep in range(2 + reps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

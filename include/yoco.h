@@ -106,9 +106,15 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
  * absolute position q_pos0 + i and attends to cache rows j <= q_pos0 + i
  * (causal). q, o: [Tq,Hq,d] of the cache dtype. Requires q_pos0 + Tq <= N_cap;
  * the rows read must have been written.
+ * workspace: optional device scratch (NULL = none), 16-byte aligned. With at
+ * least yoco_cross_attn_decode_workspace(c, Hq) bytes, a call with Tq <= 8 rows
+ * (the exit row of an early-exit prefill, Fig. 3) is split over the cache like
+ * a decode step instead of walking it with one workgroup per head. The result
+ * is the same operation either way.
  */
 int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0,
-                            int64_t Tq, int Hq, float scale, void* stream);
+                            int64_t Tq, int Hq, float scale, void* workspace, size_t workspace_bytes,
+                            void* stream);
 
 /* Workspace for yoco_cross_attn_decode on this cache with Hq query heads:
  * `splits` partial results (running max, sum, d-vector in fp32) per

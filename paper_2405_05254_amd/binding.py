@@ -40,7 +40,7 @@ def lib():
     L.yoco_kv_cache_init.argtypes = [vp, sz, i32, i32, i32, i64, i32, C.POINTER(_Cache)]
     L.yoco_swa_prefill.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i64, f32, i32, vp]
     L.yoco_global_kv_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
-    L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp]
+    L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp, sz, vp]
     L.yoco_cross_attn_decode_workspace.argtypes = [C.POINTER(_Cache), i32, C.POINTER(sz), C.POINTER(i32)]
     L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
     for name in ("yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
@@ -124,14 +124,17 @@ def global_kv_write(cache, k, v, b, pos0):
                                       b, pos0, n, _dtype(k), _stream()))
 
 
-def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None):
-    """q [Tq,Hq,d] -> o [Tq,Hq,d], causal over the cache of sequence b (yoco_cross_attn_prefill)."""
+def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None, workspace=None):
+    """q [Tq,Hq,d] -> o [Tq,Hq,d], causal over the cache of sequence b (yoco_cross_attn_prefill).
+    workspace: optional device scratch tensor (see cross_attn_decode_workspace) for few-row calls."""
     Tq, Hq, d = q.shape
     if d != cache.d or q.dtype != cache.dtype:
         raise YocoError("q does not match the cache")
     o = torch.empty_like(q) if out is None else out
+    ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().yoco_cross_attn_prefill(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), b, q_pos0, Tq, Hq, scale,
-                                         _stream()))
+                                         ws_ptr, ws_bytes, _stream()))
     return o
 
 

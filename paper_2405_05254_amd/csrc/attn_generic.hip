@@ -108,14 +108,14 @@ hipError_t launch_attn_generic(const AttnView& a, int dtype, hipStream_t s) {
 // ---- decode, pass 1 (generic): one wave per (sequence, query head, split).
 template <typename T>
 __global__ void __launch_bounds__(64) decode_generic_kernel(yoco_kv_cache c, const T* __restrict__ q,
-                                                            const int64_t* __restrict__ lens, int Hq, float scale,
-                                                            float* __restrict__ ws, int splits) {
+                                                            const int64_t* __restrict__ lens, int64_t fixed_len, int Hq,
+                                                            float scale, float* __restrict__ ws, int splits) {
   __shared__ float q_s[kMaxD];
   __shared__ float p_s[64];
   const int lane = threadIdx.x;
   const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int d = c.d, g = h / (Hq / c.Hkv);
-  int64_t len = lens[b];
+  int64_t len = lens ? lens[b] : fixed_len;         // a host-known length serves the few-row prefill case
   len = len < 0 ? 0 : (len > c.N_cap ? c.N_cap : len);
   const int64_t chunk = (len + splits - 1) / splits;
   const int64_t j_lo = sp * chunk;
@@ -135,13 +135,13 @@ __global__ void __launch_bounds__(64) decode_generic_kernel(yoco_kv_cache c, con
   }
 }
 
-hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, void* /*o*/, const int64_t* lens, int Hq,
+hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq,
                                  float scale, float* ws, int splits, hipStream_t s) {
   dim3 grid(splits, Hq, c.B);
   if (c.dtype == YOCO_F32)
-    hipLaunchKernelGGL(decode_generic_kernel<float>, grid, dim3(64), 0, s, c, (const float*)q, lens, Hq, scale, ws, splits);
+    hipLaunchKernelGGL(decode_generic_kernel<float>, grid, dim3(64), 0, s, c, (const float*)q, lens, fixed_len, Hq, scale, ws, splits);
   else
-    hipLaunchKernelGGL(decode_generic_kernel<bf16_t>, grid, dim3(64), 0, s, c, (const bf16_t*)q, lens, Hq, scale, ws, splits);
+    hipLaunchKernelGGL(decode_generic_kernel<bf16_t>, grid, dim3(64), 0, s, c, (const bf16_t*)q, lens, fixed_len, Hq, scale, ws, splits);
   return hipGetLastError();
 }
 

@@ -100,7 +100,7 @@ __device__ __forceinline__ void step(State<G>& st, const u32x4 (&kq)[G], const u
 
 template <int G, int R>
 __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
-                                                          const int64_t* __restrict__ lens, int Hq, float scale_log2,
+                                                          const int64_t* __restrict__ lens, int64_t fixed_len, int Hq, float scale_log2,
                                                           float* __restrict__ ws, int splits) {
   constexpr int kRowsPerStep = 4 * R;
   __shared__ float red_o[4][G][kD];
@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane >> 4, seg = lane & 15;
 
-  int64_t len = lens[b];
+  int64_t len = lens ? lens[b] : fixed_len;         // a host-known length serves the few-row prefill case
   len = len < 0 ? 0 : (len > c.N_cap ? c.N_cap : len);
   const int64_t chunk = (((len + splits - 1) / splits) + 127) & ~(int64_t)127;  // rows per split, 128 | chunk
   const int64_t j_lo = sp * chunk;
@@ -212,17 +212,17 @@ bool decode_bf16_supported(const yoco_kv_cache& c, int Hq) {
   return G >= 1 && G <= 4 && c.Hkv <= 65535;
 }
 
-hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int Hq, float scale,
+hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
                               float* ws, int splits, hipStream_t s) {
   dim3 grid(splits, c.Hkv, c.B), block(256);
   const float sl2 = scale * kLog2e;
   const bf16_t* qp = (const bf16_t*)q;
   constexpr int R = 8;
   switch (Hq / c.Hkv) {
-    case 1: hipLaunchKernelGGL((decode_bf16_kernel<1, R>), grid, block, 0, s, c, qp, lens, Hq, sl2, ws, splits); break;
-    case 2: hipLaunchKernelGGL((decode_bf16_kernel<2, R>), grid, block, 0, s, c, qp, lens, Hq, sl2, ws, splits); break;
-    case 3: hipLaunchKernelGGL((decode_bf16_kernel<3, R>), grid, block, 0, s, c, qp, lens, Hq, sl2, ws, splits); break;
-    case 4: hipLaunchKernelGGL((decode_bf16_kernel<4, R>), grid, block, 0, s, c, qp, lens, Hq, sl2, ws, splits); break;
+    case 1: hipLaunchKernelGGL((decode_bf16_kernel<1, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
+    case 2: hipLaunchKernelGGL((decode_bf16_kernel<2, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
+    case 3: hipLaunchKernelGGL((decode_bf16_kernel<3, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
+    case 4: hipLaunchKernelGGL((decode_bf16_kernel<4, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -37,7 +37,13 @@ namespace {
 constexpr int kD = 128;          // head dimension
 constexpr int kBN = 64;          // keys per tile
 constexpr int kNQ = 32;          // query rows per wavefront
-constexpr int kWaves = 4;
+#ifndef YOCO_SWA_WAVES
+#define YOCO_SWA_WAVES 4
+#endif
+constexpr int kWaves = YOCO_SWA_WAVES;
+constexpr int kThreads = kWaves * 64;
+constexpr int kStageRows = 1024 / kThreads;   // 16-byte chunks of a K (or V) tile per thread
+constexpr int kStageStep = kThreads / 16;     // rows between a thread's chunks
 constexpr int kBM = kNQ * kWaves;
 constexpr int kTileBytes = kBN * kD * 2;     // 16 KiB
 constexpr float kLog2e = 1.4426950408889634f;
@@ -85,7 +91,7 @@ struct Args {
   int64_t n_keys;     // keys that exist (rows beyond are never read)
 };
 
-__global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
+__global__ void __launch_bounds__(kThreads, 2) swa_mfma_kernel(Args g) {
   // Two tile buffers as distinct arrays, so that the compiler can tell the
   // stores of the next tile from the operand reads of the current one.
   __shared__ __attribute__((aligned(1024))) char k_a[kTileBytes], k_b[kTileBytes];
@@ -142,11 +148,11 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   // swizzles depend on row & 15 / row & 7 only, which 16 i does not change)
   const int kst_off = srow * 256 + ((c16 ^ (srow & 15)) << 4);
   const int vst_off = srow * 256 + (((((c16 >> 1) ^ (srow & 7)) << 1) | (c16 & 1)) << 4);
-  u32x4 kst[4], vst[4];
+  u32x4 kst[kStageRows], vst[kStageRows];
   auto load_row = [&](int jt, int i) {
     const int64_t tile_row0 = (int64_t)jt * kBN;
     const int lim = (int)(g.n_keys - 1 - tile_row0 < kBN - 1 ? g.n_keys - 1 - tile_row0 : kBN - 1);   // last row that exists
-    const int lrow = srow + 16 * i;
+    const int lrow = srow + kStageStep * i;
     const int grow = lrow < lim ? lrow : lim;             // rows past the end repeat the last one (masked later)
     const uint32_t off = (uint32_t)grow * row_bytes + (uint32_t)(c16 << 4);
     kst[i] = *(const u32x4*)((const char*)(kg + tile_row0 * a.kv_stride_n) + off);
@@ -154,13 +160,13 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   };
   auto load_tile = [&](int jt) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) load_row(jt, i);
+    for (int i = 0; i < kStageRows; ++i) load_row(jt, i);
   };
   auto store_row = [&](char* k_dst, char* v_dst, int i) {
     u32x4 vh = {bf16x2_to_f16x2(vst[i][0]), bf16x2_to_f16x2(vst[i][1]), bf16x2_to_f16x2(vst[i][2]),
                 bf16x2_to_f16x2(vst[i][3])};
-    *(u32x4*)(k_dst + kst_off + i * 4096) = kst[i];
-    *(u32x4*)(v_dst + vst_off + i * 4096) = vh;
+    *(u32x4*)(k_dst + kst_off + i * (kStageStep * 256)) = kst[i];
+    *(u32x4*)(v_dst + vst_off + i * (kStageStep * 256)) = vh;
   };
 
   // ---- Q^T fragments (B operand): lane holds query lq, dims ks*16 + hf*8 .. +8
@@ -199,7 +205,7 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
   // ---- prologue: tile of step 0 into buffer a, tile of step 1 in flight
   load_tile(tile_of(0));
 #pragma unroll
-  for (int i = 0; i < 4; ++i) store_row(k_a, v_a, i);
+  for (int i = 0; i < kStageRows; ++i) store_row(k_a, v_a, i);
   if (n_t > 1) load_tile(tile_of(1));
   __syncthreads();
   // Q is complete here; saying so keeps the loop free of waits on it (the
@@ -248,8 +254,10 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
         }
         // a staged row is published and its registers reloaded at once: the
         // loads go out one pair at a time between the products, not as a burst
-        store_row(k_nxt, v_nxt, kh);
-        load_row(jt2, kh);
+        if (kh % (4 / kStageRows) == 0) {
+          store_row(k_nxt, v_nxt, kh / (4 / kStageRows));
+          load_row(jt2, kh / (4 / kStageRows));
+        }
       }
     } else {
       if (need0) {
@@ -262,7 +270,7 @@ __global__ void __launch_bounds__(256, 2) swa_mfma_kernel(Args g) {
       }
       if (stage) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) store_row(k_nxt, v_nxt, i);
+        for (int i = 0; i < kStageRows; ++i) store_row(k_nxt, v_nxt, i);
       }
       if (prefetch) load_tile(tile_of(st + 2));
     }
@@ -362,7 +370,7 @@ hipError_t launch_swa_mfma(const AttnView& a, hipStream_t s) {
   g.n_qtiles = (int)((a.Tq + kBM - 1) / kBM);
   g.total = g.n_qtiles * a.Hq * a.B;
   g.n_keys = a.q_pos0 + a.Tq;
-  hipLaunchKernelGGL(swa_mfma_kernel, dim3(g.total), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(swa_mfma_kernel, dim3(g.total), dim3(kThreads), 0, s, g);
   return hipGetLastError();
 }
 

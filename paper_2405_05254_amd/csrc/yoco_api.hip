@@ -74,6 +74,21 @@ int decode_splits(const yoco_kv_cache* c) {
   return (int)s;
 }
 
+// Split-KV attention of one query token per sequence of `c`: pass 1 + merge.
+// `lens` (device) or, when it is null, `fixed_len` (host) gives the visible rows.
+int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
+               float* ws, int splits, hipStream_t s, const char* what) {
+  hipError_t e;
+  if (yoco::decode_bf16_supported(c, Hq))
+    e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
+  else
+    e = yoco::launch_decode_generic(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
+  if (e != hipSuccess) return hip_result(e, what);
+  return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, c.dtype, s), what);
+}
+
+constexpr int64_t kFewRows = 8;   // query rows up to which the prefill call splits over the cache like decode
+
 }  // namespace
 
 #pragma GCC visibility push(default)
@@ -154,7 +169,7 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
 }
 
 int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0, int64_t Tq, int Hq,
-                            float scale, void* stream) {
+                            float scale, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_cache(c);
   if (rc) return rc;
   rc = check_heads(Hq, c->Hkv);
@@ -168,6 +183,25 @@ int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int 
                 (long long)(q_pos0 + Tq), (long long)c->N_cap);
   const size_t eb = elem_bytes(c->dtype);
   const int64_t plane_b = (int64_t)c->Hkv * c->N_cap * c->d;
+  if (workspace && !aligned16(workspace)) return fail(YOCO_ERR_ALIGNMENT, "workspace not 16-byte aligned");
+  if (workspace && Tq <= kFewRows) {
+    // A few rows cannot fill the chip one workgroup per query tile: treat each
+    // row as a decode step of a one-sequence cache, split over the rows it sees.
+    yoco_kv_cache one = *c;
+    one.B = 1;
+    one.k = (char*)c->k + (size_t)b * plane_b * eb;
+    one.v = (char*)c->v + (size_t)b * plane_b * eb;
+    const int splits = decode_splits(&one);
+    const size_t need = (size_t)Hq * splits * yoco::partial_stride(c->d) * sizeof(float);
+    if (workspace_bytes >= need) {
+      for (int64_t i = 0; i < Tq; ++i) {
+        rc = run_decode(one, (const char*)q + (size_t)i * Hq * c->d * eb, (char*)o + (size_t)i * Hq * c->d * eb, nullptr,
+                        q_pos0 + i + 1, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "cross_attn_prefill (split)");
+        if (rc) return rc;
+      }
+      return YOCO_OK;
+    }
+  }
   yoco::AttnView a;
   a.q = q; a.o = o;
   a.k = (const char*)c->k + (size_t)b * plane_b * eb;
@@ -211,15 +245,7 @@ int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const
   rc = yoco_cross_attn_decode_workspace(c, Hq, &need, &splits);
   if (rc) return rc;
   if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
-  hipStream_t s = (hipStream_t)stream;
-  hipError_t e;
-  if (yoco::decode_bf16_supported(*c, Hq))
-    e = yoco::launch_decode_bf16(*c, q, lens, Hq, scale, (float*)workspace, splits, s);
-  else
-    e = yoco::launch_decode_generic(*c, q, o, lens, Hq, scale, (float*)workspace, splits, s);
-  if (e != hipSuccess) return hip_result(e, "cross_attn_decode pass 1");
-  return hip_result(yoco::launch_decode_merge((const float*)workspace, o, c->B, Hq, c->d, splits, c->dtype, s),
-                    "cross_attn_decode merge");
+  return run_decode(*c, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "cross_attn_decode");
 }
 
 }  // extern "C"

@@ -46,7 +46,7 @@ struct AttnView {
 
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_attn_generic(const AttnView& a, int dtype, hipStream_t s);
-hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, void* o, const int64_t* lens, int Hq,
+hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq,
                                  float scale, float* ws, int splits, hipStream_t s);
 hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, int splits, int dtype,
                                hipStream_t s);
@@ -57,7 +57,7 @@ hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v,
 bool swa_mfma_supported(const AttnView& a, int dtype);
 hipError_t launch_swa_mfma(const AttnView& a, hipStream_t s);
 bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
-hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int Hq, float scale,
+hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
                               float* ws, int splits, hipStream_t s);
 
 // Partial result of one split, per (b, h, split): o[0..d), then the running max

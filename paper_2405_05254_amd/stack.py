@@ -94,9 +94,13 @@ class YocoStack:
         return _rows(Y, lambda y: _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y)
 
     def cross_decoder_rows(self, X, cache, q_pos0):
+        ws = None
+        if X.shape[0] <= 8:          # few rows: let the call split over the cache
+            nbytes, _ = yb.cross_attn_decode_workspace(cache, self.Hq)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         for n, L in enumerate(self.cross_layers):
             def attn(q, n=n):
-                o = yb.cross_attn_prefill(cache, q, 0, q_pos0, self.scale)
+                o = yb.cross_attn_prefill(cache, q, 0, q_pos0, self.scale, workspace=ws)
                 if self.capture is not None and ("cross%d" % n) in self.capture:
                     self.capture["cross%d" % n] = (q, o)
                 return o

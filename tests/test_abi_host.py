@@ -85,9 +85,10 @@ def test_calls_validate_before_launching():
     assert L.yoco_global_kv_write(C.byref(d), None, None, 0, 5, 0, 1, None) == 0       # empty write is a no-op
     assert L.yoco_global_kv_write(None, p, p, 0, 0, 1, 1, None) == -1
     # cross_attn_prefill
-    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 98, 4, 4, 1.0, None) == -1   # beyond capacity
-    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 0, 4, 1.0, None) == -1
-    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 4, 3, 1.0, None) == -1    # Hq % Hkv
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 98, 4, 4, 1.0, None, 0, None) == -1   # beyond capacity
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 0, 4, 1.0, None, 0, None) == -1
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 4, 3, 1.0, None, 0, None) == -1    # Hq % Hkv
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 4, 4, 1.0, p + 4, 1 << 20, None) == -3   # workspace alignment
     # decode: workspace sizing and checks
     n, s = C.c_size_t(), C.c_int()
     assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(n), C.byref(s)) == 0

@@ -148,6 +148,29 @@ def test_cross_attn_prefill_matches_oracle(yoco, dtype, Hq, Hkv, d, N, q_pos0, T
     check(host(o), oracle.cross_attn(qn, ks[1], vs[1], q_pos0, scale), dtype, "cross prefill")
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,N,q_pos0,Tq", [
+    ("bf16", 6, 2, 128, 3000, 2999, 1),      # the exit row of an early-exit prefill
+    ("bf16", 6, 2, 128, 3000, 1500, 5),
+    ("bf16", 4, 4, 128, 700, 0, 8),          # rows 0..7: the first sees one key
+    ("f32", 4, 1, 64, 512, 511, 1),
+    ("bf16", 10, 2, 128, 900, 890, 3),       # G = 5: generic split kernels
+])
+def test_cross_attn_prefill_few_rows_with_workspace(yoco, dtype, Hq, Hkv, d, N, q_pos0, Tq):
+    """With a workspace, calls of up to 8 rows are split over the cache like decode;
+    the result is the same operation and is bit-identical to the decode call."""
+    scale = 1.0 / math.sqrt(d)
+    cache, ks, vs = make_cache(yoco, 2, Hkv, d, N, dtype, 60, [N, N])
+    qn = ys.normal(np.random.default_rng(61), (Tq, Hq, d), 1.0, dtype)
+    nbytes, _ = yoco.cross_attn_decode_workspace(cache, Hq)
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    o = yoco.cross_attn_prefill(cache, dev(qn, dtype), 1, q_pos0, scale, workspace=ws)
+    o_plain = yoco.cross_attn_prefill(cache, dev(qn, dtype), 1, q_pos0, scale)
+    torch.cuda.synchronize()
+    ref = oracle.cross_attn(qn, ks[1], vs[1], q_pos0, scale)
+    check(host(o), ref, dtype, "cross prefill, few rows, split")
+    check(host(o_plain), ref, dtype, "cross prefill, few rows, one workgroup per head")
+
+
 # ------------------------------------------------------------------------ decode
 DECODE_CASES = [
     # dtype, Hq, Hkv, d, N_cap, lens
