@@ -22,3 +22,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _libyoco_built():
+    """Load the in-tree libyoco.so; build it first only if nothing is built yet."""
+    from paper_2405_05254_amd import binding, build
+    if not os.path.exists(binding.lib_path()):
+        build.build_lib()
+    yield

@@ -55,6 +55,10 @@ SWA_CASES = [
     ("bf16", 1, 640, 2, 2, 128, 64, 2.0),      # window smaller than a tile, peaky softmax
     ("bf16", 1, 129, 2, 1, 128, 128, 0.5),
     ("bf16", 1, 300, 2, 2, 64, 100, 0.5),      # bf16 shape without a fast path
+    ("bf16", 1, 200, 2, 2, 128, 1, 0.5),       # window 1 on the MFMA path: o = v
+    ("bf16", 3, 130, 2, 1, 128, 40, 0.5),      # batch of ragged two-tile sequences
+    ("bf16", 1, 1500, 2, 2, 128, 700, 4.0),    # large scores: the running max keeps growing (rescale path)
+    ("bf16", 1, 5, 1, 1, 128, 3, 1.0),         # fewer rows than a wavefront
 ]
 
 
@@ -63,12 +67,24 @@ def test_swa_prefill_matches_oracle(yoco, dtype, B, T, Hq, Hkv, d, window, std):
     print("swa case", dtype, B, T, Hq, Hkv, d, window, flush=True)
     scale = 1.0 / math.sqrt(d)
     qs, ks, vs = zip(*[ys.qkv(100 + b, T, Hq, Hkv, d, std, dtype) for b in range(B)])
+    if std > 2.0:                 # large scores, unit-scale values: the absolute bound is for outputs of order 1
+        vs = tuple(v / np.float32(std) for v in vs)       # a power of two: still exact in bf16
     q, k, v = (dev(np.stack(x), dtype) for x in (qs, ks, vs))
     o = yoco.swa_prefill(q, k, v, window, scale)
     torch.cuda.synchronize()
     for b in range(B):
         ref = oracle.swa(qs[b], ks[b], vs[b], window, scale)
         check(host(o[b]), ref, dtype, "swa b=%d" % b)
+
+
+def test_swa_scale_zero_and_negative_use_the_generic_path(yoco):
+    """scale <= 0 is outside the MFMA kernel's domain (it tracks max(s) before scaling); the call still answers."""
+    T, H, d, C = 150, 2, 128, 37
+    qn, kn, vn = ys.qkv(7, T, H, H, d, 0.5, "bf16")
+    for scale in (0.0, -0.05):
+        o = yoco.swa_prefill(dev(qn[None], "bf16"), dev(kn[None], "bf16"), dev(vn[None], "bf16"), C, scale)
+        torch.cuda.synchronize()
+        check(host(o[0]), oracle.swa(qn, kn, vn, C, scale), "bf16", "swa scale %g" % scale)
 
 
 def test_swa_prefill_headline_shape_sampled(yoco):

@@ -1,0 +1,81 @@
+"""The pins must be able to fail: each plausible mistake planted in a copy of
+the oracle's attention (a wrong window bound, a dropped scale, a wrong GQA map,
+a transposed operand, a missing max shift, softmax over the wrong axis ...) is
+caught by the same kind of checks tests/test_oracle_pins.py applies to the real
+oracle (dense brute force with the literal mask, torch's library attention,
+closed forms). CPU only; nothing here touches the HIP path."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+
+
+def make_attention(window_lo=lambda i, C: max(0, i - C + 1), window_hi=lambda i: i, use_scale=True, gqa=lambda h, G: h // G,
+                   normalise=True, value_from_keys=False):
+    """A copy of the oracle's row definition with switches for planted mistakes."""
+    def attn(Q, K, V, C, scale):
+        T, Hq, _ = Q.shape
+        G = Hq // K.shape[1]
+        O = np.zeros((T, Hq, V.shape[2]))
+        for h in range(Hq):
+            g = min(gqa(h, G), K.shape[1] - 1)
+            for i in range(T):
+                j0, j1 = window_lo(i, C), min(window_hi(i), T - 1)
+                s = (scale if use_scale else 1.0) * (K[j0:j1 + 1, g] @ Q[i, h])
+                p = np.exp(s - s.max())
+                if normalise:
+                    p = p / p.sum()
+                O[i, h] = p @ (K if value_from_keys else V)[j0:j1 + 1, g]
+        return O
+    return attn
+
+
+def library_reference(Q, K, V, C, scale):
+    T = Q.shape[0]
+    G = Q.shape[1] // K.shape[1]
+    i, j = np.arange(T)[:, None], np.arange(T)[None, :]
+    band = torch.from_numpy((j <= i) & (j > i - C))
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    k = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    v = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    return F.scaled_dot_product_attention(q, k, v, attn_mask=band, scale=scale)[0].permute(1, 0, 2).numpy()
+
+
+def battery(attn):
+    """True if `attn` passes the pins (library attention on a GQA band case, window-1, equal keys)."""
+    rng = np.random.default_rng(0)
+    Q, K, V = rng.standard_normal((40, 4, 8)), rng.standard_normal((40, 2, 8)), rng.standard_normal((40, 2, 8))
+    if np.abs(attn(Q, K, V, 7, 0.6) - library_reference(Q, K, V, 7, 0.6)).max() > 1e-12:
+        return False
+    if not np.array_equal(attn(Q, K, V, 1, 0.6), np.repeat(V, 2, axis=1)):
+        return False
+    Ke = np.broadcast_to(K[:1], K.shape).copy()
+    O = attn(Q, Ke, V, 5, 0.6)
+    for i in (0, 3, 20):
+        if np.abs(O[i, 0] - V[max(0, i - 4):i + 1, 0].mean(axis=0)).max() > 1e-13:
+            return False
+    return True
+
+
+def test_the_unmutated_copy_and_the_oracle_pass():
+    assert battery(make_attention())
+    assert battery(lambda Q, K, V, C, s: oracle.swa(Q, K, V, C, s))
+
+
+MUTANTS = {
+    "window one key too long": dict(window_lo=lambda i, C: max(0, i - C)),
+    "window one key too short": dict(window_lo=lambda i, C: max(0, min(i, i - C + 2))),
+    "not causal (sees the next key)": dict(window_hi=lambda i: i + 1),
+    "scale dropped": dict(use_scale=False),
+    "GQA map interleaved instead of grouped": dict(gqa=lambda h, G: h % 2),
+    "GQA map always head 0": dict(gqa=lambda h, G: 0),
+    "softmax not normalised": dict(normalise=False),
+    "values taken from K": dict(value_from_keys=True),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_planted_mistake(name):
+    assert not battery(make_attention(**MUTANTS[name])), name
