@@ -247,20 +247,22 @@ __global__ void __launch_bounds__(kThreads, 2) swa_mfma_kernel(Args g) {
       // raised issue priority while this wavefront feeds the matrix pipe: the
       // other wavefront of the SIMD fills in with its vector work (measured -4 %)
       __builtin_amdgcn_s_setprio(2);
+      // operand fragments are read two k-steps (4 MFMAs) ahead of their use
+      bf16x8 f0[8], f1[8];
+      f0[0] = kfrag(0, 0); f1[0] = kfrag(0, 1);
+      f0[1] = kfrag(1, 0); f1[1] = kfrag(1, 1);
 #pragma unroll
-      for (int kh = 0; kh < 4; ++kh) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int ks = kh * 2 + i;
-          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 0), qf[ks], ks == 0 ? zero : s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(ks, 1), qf[ks], ks == 0 ? zero : s1, 0, 0, 0);
-        }
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks + 2 < 8) { f0[ks + 2] = kfrag(ks + 2, 0); f1[ks + 2] = kfrag(ks + 2, 1); }
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[ks], qf[ks], ks == 0 ? zero : s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks], qf[ks], ks == 0 ? zero : s1, 0, 0, 0);
         // a staged row is published and its registers reloaded at once: the
-        // loads go out one pair at a time between the products, not as a burst
-        if (kh % (4 / kStageRows) == 0) {
-          store_row(k_nxt, v_nxt, kh / (4 / kStageRows));
-          load_row(jt2, kh / (4 / kStageRows));
+        // loads go out a pair at a time between the products, not as a burst
+        if ((ks & 1) && (ks >> 1) % (4 / kStageRows) == 0) {
+          store_row(k_nxt, v_nxt, (ks >> 1) / (4 / kStageRows));
+          load_row(jt2, (ks >> 1) / (4 / kStageRows));
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_s_setprio(0);
     } else {
