@@ -11,6 +11,9 @@ routines, closed forms (equal keys -> running mean, window 1 -> V, constant V),
 locality and causality under perturbation, GQA replication, the early-exit and
 prefix invariants of the stack, and the paper's cache-size arithmetic
 (section 4.4, the KV-cache-per-token figure: 128K tokens per GB at 65B).
+The rolling-window cache and the token-by-token stack are pinned to the
+windowed definition (a literal-mask brute force over the full history) and to
+the all-at-once stack, whose outputs an autoregressive model must reproduce.
 No function here is "parity unpinned".
 
 Readings of points the paper leaves open (all listed in the design doc):
@@ -152,6 +155,73 @@ def yoco_stack(tokens, w, mode="full"):
         Y = A @ np.asarray(L["W_O"], F64) + X
         X = swiglu(rmsnorm(Y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + Y
     return rmsnorm(X, w["final_ln"], eps) @ np.asarray(w["W_out"], F64)
+
+
+class RollingWindowCache:
+    """Self-decoder cache for token-by-token generation with sliding-window
+    attention (section 3.2: the window bounds what a row can see; the footnote
+    of section 2.3 and Table 1: the self-decoder keeps O(C) rows, not O(N)).
+
+    A ring of C rows for one layer and one sequence: the row of position p is
+    kept in slot p mod C, where it replaces position p - C, which the mask
+    i - C < j <= i hides from every later row.
+    """
+
+    def __init__(self, C, Hkv, d):
+        self.C = C
+        self.K = np.zeros((C, Hkv, d), dtype=F64)
+        self.V = np.zeros((C, Hkv, d), dtype=F64)
+
+    def write(self, p, k, v):
+        """k, v [Hkv,d]: the projected row of position p."""
+        self.K[p % self.C] = k
+        self.V[p % self.C] = v
+
+    def attend(self, q, p, scale):
+        """Eq. 8 for the row at position p (already written): q [Hq,d] -> [Hq,d].
+        The visible positions max(0, p-C+1) .. p are gathered from their slots."""
+        Hq, Hkv = q.shape[0], self.K.shape[1]
+        slots = [j % self.C for j in range(max(0, p - self.C + 1), p + 1)]
+        out = np.empty((Hq, self.V.shape[2]), dtype=F64)
+        for h in range(Hq):
+            g = h // (Hq // Hkv)
+            out[h] = _softmax_weighted_sum(np.asarray(q[h], dtype=F64), self.K[slots, g], self.V[slots, g], scale)
+        return out
+
+
+def yoco_stack_generate(tokens, w):
+    """The decoder-decoder stack run one token at a time (Fig. 3 "Generation",
+    section 2.3): each self-decoder layer keeps a RollingWindowCache, Eq. 2
+    appends one row to the global cache, and the cross-decoder attends to the
+    rows written so far. Same weights dict as yoco_stack; returns the logits of
+    every position, [T,vocab], which an autoregressive model must produce
+    identically whether the prompt is processed at once or token by token."""
+    Hq, d, eps = w["Hq"], w["d"], w["eps"]
+    scale = 1.0 / np.sqrt(d)
+    rings = [RollingWindowCache(w["window"], w["Hkv_self"], d) for _ in w["self"]]
+    Khat, Vhat = [], []
+    out = []
+    for p, tok in enumerate(np.asarray(tokens)):
+        x = np.asarray(w["embed"], dtype=F64)[tok][None]              # [1,dm]
+        for L, ring in zip(w["self"], rings):
+            xn = rmsnorm(x, L["ln1"], eps)
+            q = (xn @ np.asarray(L["W_Q"], F64)).reshape(Hq, d)
+            ring.write(p, (xn @ np.asarray(L["W_K"], F64)).reshape(w["Hkv_self"], d),
+                       (xn @ np.asarray(L["W_V"], F64)).reshape(w["Hkv_self"], d))
+            a = ring.attend(q, p, scale).reshape(1, Hq * d)
+            y = a @ np.asarray(L["W_O"], F64) + x
+            x = swiglu(rmsnorm(y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + y
+        kh, vh = global_kv(x, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)
+        Khat.append(kh[0])
+        Vhat.append(vh[0])
+        Kc, Vc = np.stack(Khat), np.stack(Vhat)
+        for L in w["cross"]:
+            qh = (rmsnorm(x, L["ln1"], eps) @ np.asarray(L["W_Q"], F64)).reshape(1, Hq, d)
+            a = cross_attn(qh, Kc, Vc, p, scale).reshape(1, Hq * d)
+            y = a @ np.asarray(L["W_O"], F64) + x
+            x = swiglu(rmsnorm(y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + y
+        out.append((rmsnorm(x, w["final_ln"], eps) @ np.asarray(w["W_out"], F64))[0])
+    return np.stack(out)
 
 
 def kv_cache_bytes_per_token(Hkv, d, elem_bytes, cached_layers=1):

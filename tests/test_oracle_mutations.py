@@ -79,3 +79,52 @@ MUTANTS = {
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_pins_catch_planted_mistake(name):
     assert not battery(make_attention(**MUTANTS[name])), name
+
+
+# ---- the rolling-window cache: planted mistakes in a copy of the ring
+def make_ring_attention(slot=lambda p, C: p % C, first=lambda p, C: max(0, p - C + 1), slots_in_ring=lambda C: C):
+    """Attention through a ring of slots, as a function with the signature of
+    the battery's `attn`, with switches for planted mistakes."""
+    def attn(Q, K, V, C, scale):
+        T, Hq, _ = Q.shape
+        G = Hq // K.shape[1]
+        n = slots_in_ring(C)
+        Kr, Vr = np.zeros((n,) + K.shape[1:]), np.zeros((n,) + V.shape[1:])
+        O = np.zeros((T, Hq, V.shape[2]))
+        for p in range(T):
+            Kr[slot(p, C) % n], Vr[slot(p, C) % n] = K[p], V[p]
+            idx = [slot(j, C) % n for j in range(first(p, C), p + 1)]
+            for h in range(Hq):
+                s = scale * (Kr[idx, h // G] @ Q[p, h])
+                w = np.exp(s - s.max())
+                O[p, h] = (w / w.sum()) @ Vr[idx, h // G]
+        return O
+    return attn
+
+
+def oracle_ring(Q, K, V, C, scale):
+    ring = oracle.RollingWindowCache(C, K.shape[1], K.shape[2])
+    out = []
+    for p in range(Q.shape[0]):
+        ring.write(p, K[p], V[p])
+        out.append(ring.attend(Q[p], p, scale))
+    return np.stack(out)
+
+
+def test_the_unmutated_ring_and_the_oracle_ring_pass():
+    assert battery(make_ring_attention())
+    assert battery(oracle_ring)
+
+
+RING_MUTANTS = {
+    "slot = p mod (C+1) with C slots": dict(slot=lambda p, C: p % (C + 1)),
+    "ring one slot short": dict(slots_in_ring=lambda C: max(1, C - 1)),
+    "gathers C+1 positions": dict(first=lambda p, C: max(0, p - C)),
+    "gathers C-1 positions": dict(first=lambda p, C: max(0, min(p, p - C + 2))),
+    "slot order reversed": dict(slot=lambda p, C: C - 1 - p % C, first=lambda p, C: max(0, p - C)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(RING_MUTANTS))
+def test_pins_catch_planted_ring_mistake(name):
+    assert not battery(make_ring_attention(**RING_MUTANTS[name])), name

@@ -241,6 +241,60 @@ def test_prefix_invariance_decoder_only_behaviour():
         assert np.abs(short[0] - full[t]).max() < 1e-12
 
 
+# ------------------------------------- rolling-window cache (section 3.2, 2.3 footnote)
+@pytest.mark.parametrize("T,C", [(23, 5), (9, 1), (12, 12), (7, 30), (33, 8)])
+def test_rolling_cache_matches_brute_force_over_full_history(T, C):
+    """Feeding the rows one by one through a ring of C slots gives, at every
+    position (before the first wrap, at it, and several wraps later), the row of
+    the literal-mask definition computed over the whole history."""
+    Q, K, V = rand_qkv(11, T, 4, 2, 8)
+    ref = brute_force(Q, K, V, lambda i, j: i - C < j <= i, 0.41)
+    ring = oracle.RollingWindowCache(C, 2, 8)
+    assert ring.K.shape == (C, 2, 8) and ring.V.shape == (C, 2, 8)      # O(C) rows whatever T is
+    for p_ in range(T):
+        ring.write(p_, K[p_], V[p_])
+        assert np.abs(ring.attend(Q[p_], p_, 0.41) - ref[p_]).max() < 1e-12, p_
+
+
+def test_rolling_cache_forgets_exactly_position_p_minus_C():
+    """After position p is written, changing the history at p - C (overwritten)
+    cannot matter, while changing p - C + 1 (the oldest kept row) must."""
+    C, T = 6, 20
+    Q, K, V = rand_qkv(12, T, 2, 2, 8)
+
+    def last_row(Kx, Vx):
+        ring = oracle.RollingWindowCache(C, 2, 8)
+        for p_ in range(T):
+            ring.write(p_, Kx[p_], Vx[p_])
+        return ring.attend(Q[T - 1], T - 1, 0.5)
+
+    base = last_row(K, V)
+    K2, V2 = K.copy(), V.copy()
+    K2[T - 1 - C] += 3.0
+    V2[T - 1 - C] -= 2.0
+    assert np.array_equal(last_row(K2, V2), base)
+    V3 = V.copy()
+    V3[T - C] += 1.0
+    assert np.abs(last_row(K, V3) - base).max() > 1e-3
+
+
+def test_token_by_token_stack_equals_all_at_once_stack():
+    """An autoregressive model gives the same logits whether the prompt is
+    processed at once or one token at a time (sections 2 and 2.3); the sequence
+    is several windows long so the rings wrap."""
+    w = ys.stack_weights(2, SMALL, "f32")
+    for k in ("self", "cross"):
+        for L in w[k]:
+            for n in ("W_Q", "W_K", "W_V"):
+                if n in L:
+                    L[n] = L[n] * 30
+    tok = ys.tokens(2, 29, 50)
+    full = oracle.yoco_stack(tok, w, "full")
+    step = oracle.yoco_stack_generate(tok, w)
+    assert step.shape == full.shape
+    assert np.abs(step - full).max() < 1e-11
+
+
 def test_stack_matches_library_composition():
     """The same stack assembled from torch library ops (rms_norm, sdpa with
     masks, silu) in float64."""
