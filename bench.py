@@ -155,6 +155,40 @@ def main():
                                 cache_bytes=int(cache_bytes))
             del kvc, Kp, Vp, w, qs
             torch.cuda.empty_cache()
+        # one generation step of the self-decoder: 13 layers, each appends the new row to its own rolling
+        # window cache (window 1024, 24 heads) and attends to it, 16 sequences at position 32767
+        sc = ys.CONFIGS["swa_prefill_32k"]
+        B, Cw, Hs, layers = 16, sc["window"], sc["Hq"], 13
+        rings = [yoco.KVCache(B, Hs, d, Cw, torch.bfloat16) for _ in range(layers)]
+        for i, r in enumerate(rings):
+            for pl in r.planes():
+                pl.copy_(ys.device_normal(pl.shape, 300 + i, 1.0, torch.bfloat16, dev))
+        qs = [ys.device_normal((B, Hs, d), 400 + i, 1.0, torch.bfloat16, dev) for i in range(layers)]
+        kn = ys.device_normal((B, Hs, d), 500, 1.0, torch.bfloat16, dev)
+        od = torch.empty_like(qs[0])
+        pos = torch.full((B,), 32767, dtype=torch.int64, device=dev)
+        ln = pos + 1
+        nb, splits = yoco.cross_attn_decode_workspace(rings[0], Hs)
+        w = torch.empty(nb, dtype=torch.uint8, device=dev)
+        times = []
+        for rep in range(2 + max(3, min(20, args.steps // 2))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(layers):
+                yoco.kv_cache_append(rings[i], kn, kn, pos, True)
+                yoco.swa_decode(rings[i], qs[i], ln, scale, w, out=od)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                times.append(e0.elapsed_time(e1))
+        ms = sum(times) / len(times)
+        ring_bytes = 2.0 * B * Cw * Hs * d * 2
+        gbs = layers * ring_bytes / (ms * 1e-3) / 1e9
+        decode["swa_decode_b16_w1024"] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4),
+                                              GBps=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4),
+                                              splits=splits, ring_bytes_per_layer=int(ring_bytes))
+        del rings, qs, w
+        torch.cuda.empty_cache()
 
     # ---- the oracle on the host cores, bounded sample of the same SWA workload
     cpu = None

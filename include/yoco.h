@@ -2,7 +2,7 @@
  * libyoco -- the attention hot path of YOCO ("You Only Cache Once",
  * arXiv 2405.05254) for AMD MI355X (gfx950).
  *
- * Four operations, each a hand-written HIP kernel behind a plain C ABI:
+ * Operations, each a hand-written HIP kernel behind a plain C ABI:
  *   yoco_swa_prefill          sliding-window attention of the self-decoder
  *                             (section 3.2, Eq. 8)
  *   yoco_global_kv_write      store rows of the once-only global K^/V^ cache
@@ -11,6 +11,10 @@
  *                             global cache (section 2.2, Eq. 3)
  *   yoco_cross_attn_decode    the same for one new token per sequence, split
  *                             over the cache and merged by log-sum-exp
+ *   yoco_swa_cache_write, yoco_kv_cache_append, yoco_swa_decode
+ *                             token-by-token generation: the self-decoder's
+ *                             rolling window cache (section 3.2) and batched
+ *                             one-row appends
  *
  * Conventions
  *   - Every pointer named q/k/v/o/lens/workspace/mem is DEVICE memory owned by
@@ -133,6 +137,52 @@ int yoco_cross_attn_decode_workspace(const yoco_kv_cache* c, int Hq, size_t* byt
  */
 int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const int64_t* lens, int Hq,
                            float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Token-by-token generation through the self-decoder ----
+ * Sliding-window attention needs only the last C rows of a layer's K and V
+ * (section 3.2, Eq. 8; the footnote of section 2.3 and Table 1 count this
+ * cache as O(C) per self-decoder layer, constant in the sequence length).
+ * The rolling cache is a yoco_kv_cache whose N_cap is the window C, used as a
+ * ring: the row of position p lives in slot p mod C, where it replaces
+ * position p - C, which no later row can see. One such cache per
+ * self-decoder layer; yoco_kv_cache_bytes / _init size and describe it.
+ */
+
+/*
+ * Store n rows K[pos0..pos0+n), V[pos0..pos0+n) of sequence b into a rolling
+ * cache (after a prefill: the rows a later decode step can still see).
+ * k, v: [n,Hkv,d] of `src_dtype`. Row pos0 + r goes to slot (pos0 + r) mod
+ * N_cap; when n > N_cap only the last N_cap rows are stored. pos0 >= 0,
+ * 0 <= b < B; n == 0 is a no-op.
+ */
+int yoco_swa_cache_write(const yoco_kv_cache* ring, const void* k, const void* v, int b, int64_t pos0,
+                         int64_t n, int src_dtype, void* stream);
+
+/*
+ * Append one row per sequence, at positions known only on the device (a decode
+ * step of a batch whose sequences have different lengths). k, v: [B,Hkv,d] of
+ * `src_dtype`; pos: device int64 [B]. Sequence b's row goes to slot pos[b]
+ * (ring == 0: the global cache of Eq. 2) or pos[b] mod N_cap (ring != 0: a
+ * rolling cache). A sequence with pos[b] < 0, or with pos[b] >= N_cap when
+ * ring == 0, is skipped (nothing is written for it).
+ */
+int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, const int64_t* pos, int ring,
+                         int src_dtype, void* stream);
+
+/*
+ * One decode step of a self-decoder layer: Eq. 8 for one new token per
+ * sequence. q, o: [B,Hq,d] of the cache dtype. lens: device int64 [B], the
+ * number of tokens of sequence b so far including the new one, whose row has
+ * been appended before the call (the mask includes j = i). The row attends to
+ * the min(lens[b], N_cap) rows the ring holds, which are exactly positions
+ * lens[b]-N_cap .. lens[b]-1; the order of the slots is irrelevant to a
+ * softmax-weighted sum. Same two passes, workspace
+ * (yoco_cross_attn_decode_workspace on this ring) and reproducibility as
+ * yoco_cross_attn_decode.
+ */
+int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int64_t* lens, int Hq, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). */
 const char* yoco_last_error_string(void);

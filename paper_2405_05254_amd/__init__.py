@@ -8,4 +8,5 @@ from .binding import (  # noqa: F401
     F32, BF16, YocoError, KVCache, lib, lib_path,
     kv_cache_bytes, swa_prefill, global_kv_write, cross_attn_prefill,
     cross_attn_decode, cross_attn_decode_workspace, version,
+    swa_cache_write, kv_cache_append, swa_decode,
 )

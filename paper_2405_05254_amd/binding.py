@@ -43,8 +43,12 @@ def lib():
     L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp, sz, vp]
     L.yoco_cross_attn_decode_workspace.argtypes = [C.POINTER(_Cache), i32, C.POINTER(sz), C.POINTER(i32)]
     L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
+    L.yoco_swa_cache_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
+    L.yoco_kv_cache_append.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, i32, vp]
+    L.yoco_swa_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
     for name in ("yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
-                 "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode"):
+                 "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode",
+                 "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode"):
         getattr(L, name).restype = i32
     _LIB = L
     return L
@@ -86,7 +90,8 @@ def kv_cache_bytes(B, Hkv, d, N_cap, dtype):
 
 
 class KVCache:
-    """The once-only global K^/V^ cache: torch owns the memory, the descriptor is yoco_kv_cache."""
+    """The once-only global K^/V^ cache, or (N_cap = window) the rolling cache of one self-decoder layer:
+    torch owns the memory, the descriptor is yoco_kv_cache."""
 
     def __init__(self, B, Hkv, d, N_cap, dtype=torch.bfloat16, device="cuda"):
         code = F32 if dtype == torch.float32 else BF16
@@ -155,4 +160,37 @@ def cross_attn_decode(cache, q, lens, scale, workspace, out=None):
     _check(lib().yoco_cross_attn_decode(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq,
                                         scale, _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                         _stream()))
+    return o
+
+
+def swa_cache_write(ring, k, v, b, pos0):
+    """k, v [n,Hkv,d] rows of positions pos0.. -> ring slots (pos0 + r) mod N_cap of sequence b (yoco_swa_cache_write)."""
+    n = k.shape[0]
+    if n and (k.shape != (n, ring.Hkv, ring.d) or v.shape != k.shape or v.dtype != k.dtype):
+        raise YocoError("k/v rows do not match the cache")
+    _check(lib().yoco_swa_cache_write(C.byref(ring.desc), _dev(k, "k") if n else None, _dev(v, "v") if n else None,
+                                      b, pos0, n, _dtype(k), _stream()))
+
+
+def kv_cache_append(cache, k, v, pos, ring):
+    """k, v [B,Hkv,d], pos int64 [B] (device): one row per sequence at slot pos[b] (mod N_cap if ring)
+    (yoco_kv_cache_append)."""
+    if k.shape != (cache.B, cache.Hkv, cache.d) or v.shape != k.shape or v.dtype != k.dtype:
+        raise YocoError("k/v rows do not match the cache")
+    if pos.dtype != torch.int64 or pos.shape != (cache.B,):
+        raise YocoError("pos must be int64 [B]")
+    _check(lib().yoco_kv_cache_append(C.byref(cache.desc), _dev(k, "k"), _dev(v, "v"), _dev(pos, "pos"), int(bool(ring)),
+                                      _dtype(k), _stream()))
+
+
+def swa_decode(ring, q, lens, scale, workspace, out=None):
+    """q [B,Hq,d], lens int64 [B] (device, tokens so far including the new one) -> o [B,Hq,d] (yoco_swa_decode)."""
+    B, Hq, d = q.shape
+    if B != ring.B or d != ring.d or q.dtype != ring.dtype:
+        raise YocoError("q does not match the cache")
+    if lens.dtype != torch.int64 or lens.shape != (B,):
+        raise YocoError("lens must be int64 [B]")
+    o = torch.empty_like(q) if out is None else out
+    _check(lib().yoco_swa_decode(C.byref(ring.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq, scale,
+                                 _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
     return o

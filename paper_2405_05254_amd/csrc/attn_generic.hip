@@ -251,18 +251,25 @@ __device__ __forceinline__ void store8(bf16_t* p, const Row8<float>& r) {
   *(kvw_u32x4*)p = w;
 }
 
+// Rows r0 .. n-1 of k, v [n,Hkv,d] -> cache rows of sequence b. Row r goes to
+// slot pos0 + r, taken modulo N_cap: the identity for the global cache (the
+// host has checked pos0 + n <= N_cap), the ring slot for a rolling cache
+// (whose caller passes r0 = max(0, n - N_cap), so no two rows share a slot).
 template <typename S, typename D>
 __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S* __restrict__ k,
-                                                       const S* __restrict__ v, int b, int64_t pos0, int64_t n) {
+                                                       const S* __restrict__ v, int b, int64_t pos0, int64_t r0,
+                                                       int64_t n) {
   const int d8 = c.d / 8;
-  const int64_t total = n * c.Hkv * d8;                  // groups of 8 elements
+  const int64_t total = (n - r0) * c.Hkv * d8;           // groups of 8 elements
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int e8 = (int)(idx % d8);
     const int g = (int)((idx / d8) % c.Hkv);
-    const int64_t r = idx / ((int64_t)d8 * c.Hkv);
+    const int64_t r = r0 + idx / ((int64_t)d8 * c.Hkv);
+    int64_t slot = pos0 + r;
+    if (slot >= c.N_cap) slot %= c.N_cap;
     const int64_t src = (r * c.Hkv + g) * c.d + e8 * 8;
-    const int64_t dst = (((int64_t)b * c.Hkv + g) * c.N_cap + pos0 + r) * c.d + e8 * 8;
+    const int64_t dst = (((int64_t)b * c.Hkv + g) * c.N_cap + slot) * c.d + e8 * 8;
     Row8<S> kr, vr;
     kr.load(k + src);
     vr.load(v + src);
@@ -271,20 +278,67 @@ __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S*
   }
 }
 
-hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
-                           int src_dtype, hipStream_t s) {
-  const int64_t total = n * c.Hkv * (c.d / 8);
+// One row per sequence at a device-side position: k, v [B,Hkv,d]; sequence b's
+// row goes to slot pos[b] (ring: modulo N_cap). Out-of-range positions write
+// nothing.
+template <typename S, typename D>
+__global__ void __launch_bounds__(256) kv_append_kernel(yoco_kv_cache c, const S* __restrict__ k,
+                                                        const S* __restrict__ v, const int64_t* __restrict__ pos,
+                                                        int ring) {
+  const int d8 = c.d / 8;
+  const int64_t total = (int64_t)c.B * c.Hkv * d8;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int e8 = (int)(idx % d8);
+    const int g = (int)((idx / d8) % c.Hkv);
+    const int b = (int)(idx / ((int64_t)d8 * c.Hkv));
+    int64_t slot = pos[b];
+    if (slot < 0) continue;
+    if (slot >= c.N_cap) {
+      if (!ring) continue;
+      slot %= c.N_cap;
+    }
+    const int64_t src = ((int64_t)b * c.Hkv + g) * c.d + e8 * 8;
+    const int64_t dst = (((int64_t)b * c.Hkv + g) * c.N_cap + slot) * c.d + e8 * 8;
+    Row8<S> kr, vr;
+    kr.load(k + src);
+    vr.load(v + src);
+    store8((D*)c.k + dst, kr);
+    store8((D*)c.v + dst, vr);
+  }
+}
+
+hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t r0,
+                           int64_t n, int src_dtype, hipStream_t s) {
+  const int64_t total = (n - r0) * c.Hkv * (c.d / 8);
   int64_t blocks = (total + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   dim3 grid((unsigned)blocks), block(256);
   if (src_dtype == YOCO_F32 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_write_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, n);
+    hipLaunchKernelGGL((kv_write_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, r0, n);
   else if (src_dtype == YOCO_F32 && c.dtype == YOCO_BF16)
-    hipLaunchKernelGGL((kv_write_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, n);
+    hipLaunchKernelGGL((kv_write_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, r0, n);
   else if (src_dtype == YOCO_BF16 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_write_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, n);
+    hipLaunchKernelGGL((kv_write_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, r0, n);
   else
-    hipLaunchKernelGGL((kv_write_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, n);
+    hipLaunchKernelGGL((kv_write_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, r0, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int ring,
+                            int src_dtype, hipStream_t s) {
+  const int64_t total = (int64_t)c.B * c.Hkv * (c.d / 8);
+  int64_t blocks = (total + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  dim3 grid((unsigned)blocks), block(256);
+  if (src_dtype == YOCO_F32 && c.dtype == YOCO_F32)
+    hipLaunchKernelGGL((kv_append_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, ring);
+  else if (src_dtype == YOCO_F32 && c.dtype == YOCO_BF16)
+    hipLaunchKernelGGL((kv_append_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, ring);
+  else if (src_dtype == YOCO_BF16 && c.dtype == YOCO_F32)
+    hipLaunchKernelGGL((kv_append_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, ring);
+  else
+    hipLaunchKernelGGL((kv_append_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, ring);
   return hipGetLastError();
 }
 

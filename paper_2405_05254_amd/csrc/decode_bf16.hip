@@ -101,7 +101,7 @@ __device__ __forceinline__ void step(State<G>& st, const u32x4 (&kq)[G], const u
 template <int G, int R>
 __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
                                                           const int64_t* __restrict__ lens, int64_t fixed_len, int Hq, float scale_log2,
-                                                          float* __restrict__ ws, int splits) {
+                                                          float* __restrict__ ws, int splits, bf16_t* __restrict__ o_direct) {
   constexpr int kRowsPerStep = 4 * R;
   __shared__ float red_o[4][G][kD];
   __shared__ float red_ml[4][G][2];
@@ -195,6 +195,10 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
       l = fmaf(f, red_ml[w][h][1], l);
       o = fmaf(f, red_o[w][h][e], o);
     }
+    if (o_direct) {          // a single split is the whole answer: normalise and store, no merge pass
+      o_direct[((size_t)b * Hq + g * G + h) * kD + e] = f32_to_bf16(l > 0.f ? o / l : 0.f);
+      continue;
+    }
     float* out = ws + (((size_t)b * Hq + g * G + h) * splits + sp) * partial_stride(kD);
     out[e] = o;
     if (e == 0) {
@@ -213,16 +217,17 @@ bool decode_bf16_supported(const yoco_kv_cache& c, int Hq) {
 }
 
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
-                              float* ws, int splits, hipStream_t s) {
+                              float* ws, int splits, void* o_direct, hipStream_t s) {
+  bf16_t* od = splits == 1 ? (bf16_t*)o_direct : nullptr;
   dim3 grid(splits, c.Hkv, c.B), block(256);
   const float sl2 = scale * kLog2e;
   const bf16_t* qp = (const bf16_t*)q;
   constexpr int R = 8;
   switch (Hq / c.Hkv) {
-    case 1: hipLaunchKernelGGL((decode_bf16_kernel<1, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
-    case 2: hipLaunchKernelGGL((decode_bf16_kernel<2, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
-    case 3: hipLaunchKernelGGL((decode_bf16_kernel<3, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
-    case 4: hipLaunchKernelGGL((decode_bf16_kernel<4, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits); break;
+    case 1: hipLaunchKernelGGL((decode_bf16_kernel<1, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
+    case 2: hipLaunchKernelGGL((decode_bf16_kernel<2, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
+    case 3: hipLaunchKernelGGL((decode_bf16_kernel<3, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
+    case 4: hipLaunchKernelGGL((decode_bf16_kernel<4, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -79,9 +79,10 @@ int decode_splits(const yoco_kv_cache* c) {
 int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
                float* ws, int splits, hipStream_t s, const char* what) {
   hipError_t e;
-  if (yoco::decode_bf16_supported(c, Hq))
-    e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
-  else
+  if (yoco::decode_bf16_supported(c, Hq)) {
+    e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, o, s);
+    if (splits == 1) return hip_result(e, what);      // one split: pass 1 wrote the output
+  } else
     e = yoco::launch_decode_generic(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
   if (e != hipSuccess) return hip_result(e, what);
   return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, c.dtype, s), what);
@@ -165,7 +166,34 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
   if (n == 0) return YOCO_OK;
   if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
-  return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
+  return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, 0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
+}
+
+int yoco_swa_cache_write(const yoco_kv_cache* ring, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+                         int src_dtype, void* stream) {
+  int rc = check_cache(ring);
+  if (rc) return rc;
+  if (n < 0) return fail(YOCO_ERR_INVALID_ARG, "negative row count");
+  if (b < 0 || b >= ring->B) return fail(YOCO_ERR_INVALID_ARG, "sequence %d outside [0, %d)", b, ring->B);
+  if (pos0 < 0) return fail(YOCO_ERR_INVALID_ARG, "negative position %lld", (long long)pos0);
+  if (pos0 > INT64_MAX - n) return fail(YOCO_ERR_INVALID_ARG, "positions overflow");
+  if (!dtype_ok(src_dtype)) return fail(YOCO_ERR_UNSUPPORTED, "source dtype %d", src_dtype);
+  if (n == 0) return YOCO_OK;
+  if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
+  if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
+  const int64_t r0 = n > ring->N_cap ? n - ring->N_cap : 0;     // earlier rows would be overwritten by later ones
+  return hip_result(yoco::launch_kv_write(*ring, k, v, b, pos0, r0, n, src_dtype, (hipStream_t)stream), "swa_cache_write");
+}
+
+int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, const int64_t* pos, int ring,
+                         int src_dtype, void* stream) {
+  int rc = check_cache(c);
+  if (rc) return rc;
+  if (!dtype_ok(src_dtype)) return fail(YOCO_ERR_UNSUPPORTED, "source dtype %d", src_dtype);
+  if (!k || !v || !pos) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
+  if (((uintptr_t)pos) & 7u) return fail(YOCO_ERR_ALIGNMENT, "pos is not 8-byte aligned");
+  return hip_result(yoco::launch_kv_append(*c, k, v, pos, ring, src_dtype, (hipStream_t)stream), "kv_cache_append");
 }
 
 int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0, int64_t Tq, int Hq,
@@ -246,6 +274,27 @@ int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const
   if (rc) return rc;
   if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
   return run_decode(*c, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "cross_attn_decode");
+}
+
+int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int64_t* lens, int Hq, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  // The ring holds exactly the rows the window admits and a softmax-weighted
+  // sum does not depend on the order of its terms, so a decode step over the
+  // ring, with lens clamped to its capacity (the kernels do), is Eq. 8.
+  int rc = check_cache(ring);
+  if (rc) return rc;
+  rc = check_heads(Hq, ring->Hkv);
+  if (rc) return rc;
+  if (!q || !o || !lens || !workspace) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(q) || !aligned16(o) || !aligned16(workspace))
+    return fail(YOCO_ERR_ALIGNMENT, "pointer not 16-byte aligned");
+  if (ring->B > 65535) return fail(YOCO_ERR_UNSUPPORTED, "B %d exceeds the grid limit", ring->B);
+  size_t need = 0;
+  int splits = 0;
+  rc = yoco_cross_attn_decode_workspace(ring, Hq, &need, &splits);
+  if (rc) return rc;
+  if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
+  return run_decode(*ring, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "swa_decode");
 }
 
 }  // extern "C"

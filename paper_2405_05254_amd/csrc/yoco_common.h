@@ -50,15 +50,18 @@ hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, const in
                                  float scale, float* ws, int splits, hipStream_t s);
 hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, int splits, int dtype,
                                hipStream_t s);
-hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
-                           int src_dtype, hipStream_t s);
+hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t r0,
+                           int64_t n, int src_dtype, hipStream_t s);
+hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int ring,
+                            int src_dtype, hipStream_t s);
 
 // bf16, d = 128 fast paths. `supported` functions are host-side predicates.
 bool swa_mfma_supported(const AttnView& a, int dtype);
 hipError_t launch_swa_mfma(const AttnView& a, hipStream_t s);
 bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
+// With one split and a non-null o_direct the kernel normalises and stores the output itself (no merge pass).
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
-                              float* ws, int splits, hipStream_t s);
+                              float* ws, int splits, void* o_direct, hipStream_t s);
 
 // Partial result of one split, per (b, h, split): o[0..d), then the running max
 // m (natural-log units) and sum l, padded so every row starts 16-byte aligned.

@@ -1,5 +1,5 @@
-"""YOCO decoder-decoder stack for the end-to-end early-exit check (section 2,
-Eq. 1-3, Fig. 2 and 3). Attention runs in libyoco; RMSNorm, the projections,
+"""YOCO decoder-decoder stack for the end-to-end early-exit and generation
+checks (section 2, Eq. 1-3, Fig. 2 and 3). Attention runs in libyoco; RMSNorm, the projections,
 SwiGLU and the classifier are plain torch ops on the GPU (the non-attention
 GEMMs are not part of the library).
 
@@ -57,7 +57,8 @@ class YocoStack:
         self.final_ln, self.W_out = dev(w["final_ln"]), dev(w["W_out"])
 
     # -- self-decoder: Eq. 1 with sliding-window attention (Eq. 8)
-    def self_decoder(self, tokens):
+    def self_decoder(self, tokens, rings=None):
+        """rings: optional list of rolling caches (one per layer) that receive the last `window` K/V rows."""
         X = self.embed[tokens]
         T = X.shape[0]
         for n, L in enumerate(self.self_layers):
@@ -66,6 +67,8 @@ class YocoStack:
             k = (xn @ L["W_K"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
             v = (xn @ L["W_V"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
             o = yb.swa_prefill(q, k, v, self.window, self.scale)
+            if rings is not None:
+                yb.swa_cache_write(rings[n], k[0], v[0], 0, 0)
             if self.capture is not None and ("self%d" % n) in self.capture:
                 self.capture["self%d" % n] = (q[0], k[0], v[0], o[0])
             Y = o.view(T, self.Hq * self.d).to(self.glue) @ L["W_O"] + X
@@ -139,3 +142,51 @@ class YocoStack:
         else:
             x_last = self.cross_decoder_rows(x_last, cache, T - 1)
         return self.logits(x_last), cache
+
+    # -- token-by-token generation (Fig. 3 "Generation"): rolling caches in the self-decoder
+    def new_generation_state(self, max_len):
+        """Caches of one sequence: a ring of `window` rows per self-decoder layer and the global cache."""
+        rings = [yb.KVCache(1, self.Hkv_self, self.d, self.window, self.dtype, self.device) for _ in self.self_layers]
+        cache = yb.KVCache(1, self.Hkv, self.d, max_len, self.dtype, self.device)
+        ws = []
+        for c, Hq in ((rings[0], self.Hq), (cache, self.Hq)):
+            nbytes, _ = yb.cross_attn_decode_workspace(c, Hq)
+            ws.append(torch.empty(nbytes, dtype=torch.uint8, device=self.device))
+        return dict(rings=rings, cache=cache, ws_ring=ws[0], ws_cache=ws[1], length=0)
+
+    def prefill(self, tokens, state):
+        """Early-exit prefill of a prompt (state must be fresh); returns the logits of its last position."""
+        assert state["length"] == 0
+        X = self.self_decoder(tokens, rings=state["rings"])
+        T = X.shape[0]
+        self.write_cache(X, state["cache"], 0)
+        state["length"] = T
+        lens = torch.tensor([T], dtype=torch.int64, device=self.device)
+        x = X[T - 1:T].contiguous()
+        for L in self.cross_layers:
+            x = self._cross_layer(x, L, lambda q: yb.cross_attn_decode(state["cache"], q, lens, self.scale, state["ws_cache"]))
+        return self.logits(x)
+
+    def decode_step(self, token, state):
+        """One new token through both decoders; returns its logits [1,vocab]."""
+        p = state["length"]
+        pos = torch.tensor([p], dtype=torch.int64, device=self.device)
+        lens = pos + 1
+        x = self.embed[torch.as_tensor(token, device=self.device).view(1)]
+        for L, ring in zip(self.self_layers, state["rings"]):
+            xn = _rmsnorm(x, L["ln1"], self.eps)
+            q = (xn @ L["W_Q"]).to(self.dtype).view(1, self.Hq, self.d)
+            k = (xn @ L["W_K"]).to(self.dtype).view(1, self.Hkv_self, self.d)
+            v = (xn @ L["W_V"]).to(self.dtype).view(1, self.Hkv_self, self.d)
+            yb.kv_cache_append(ring, k, v, pos, True)
+            o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"])
+            y = o.view(1, self.Hq * self.d).to(self.glue) @ L["W_O"] + x
+            x = _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y
+        xn = _rmsnorm(x, self.kv["ln"], self.eps)
+        k = (xn @ self.kv["W_K"]).to(self.dtype).view(1, self.Hkv, self.d)
+        v = (xn @ self.kv["W_V"]).to(self.dtype).view(1, self.Hkv, self.d)
+        yb.kv_cache_append(state["cache"], k, v, pos, False)
+        for L in self.cross_layers:
+            x = self._cross_layer(x, L, lambda q: yb.cross_attn_decode(state["cache"], q, lens, self.scale, state["ws_cache"]))
+        state["length"] = p + 1
+        return self.logits(x)

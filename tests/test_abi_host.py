@@ -108,3 +108,32 @@ def test_decode_splits_fill_the_chip():
         assert L.yoco_cross_attn_decode_workspace(C.byref(d), 24, C.byref(n), C.byref(s)) == 0
         assert B * 8 * s.value >= 256           # at least one workgroup per CU (256 CUs)
         assert n.value < 0.01 * 2 * B * 8 * N * 128 * 2   # partials cost < 1 % of the cache bytes
+
+
+def test_generation_calls_validate_before_launching():
+    """The rolling-cache entry points: host-side failures only (no GPU here)."""
+    L = yoco.lib()
+    p = 0x7f0000000000
+    d = yb._Cache()
+    need = yoco.kv_cache_bytes(2, 2, 64, 16, yoco.BF16)
+    assert L.yoco_kv_cache_init(p, need, 2, 2, 64, 16, yoco.BF16, C.byref(d)) == 0
+    # swa_cache_write: positions may exceed the capacity (it is a ring), but not be negative
+    assert L.yoco_swa_cache_write(C.byref(d), p, p, 0, -1, 1, 1, None) == -1
+    assert L.yoco_swa_cache_write(C.byref(d), p, p, 2, 0, 1, 1, None) == -1             # b out of range
+    assert L.yoco_swa_cache_write(C.byref(d), p, p, 0, 0, -3, 1, None) == -1
+    assert L.yoco_swa_cache_write(C.byref(d), p, p + 8, 0, 0, 4, 1, None) == -3
+    assert L.yoco_swa_cache_write(C.byref(d), p, p, 0, 0, 4, 7, None) == -2             # dtype
+    assert L.yoco_swa_cache_write(C.byref(d), None, None, 0, 1000, 0, 1, None) == 0      # empty write is a no-op
+    assert L.yoco_swa_cache_write(None, p, p, 0, 0, 1, 1, None) == -1
+    # kv_cache_append
+    assert L.yoco_kv_cache_append(C.byref(d), p, p, None, 1, 1, None) == -1
+    assert L.yoco_kv_cache_append(C.byref(d), p, p, p + 4, 1, 1, None) == -3            # pos alignment
+    assert L.yoco_kv_cache_append(C.byref(d), p + 2, p, p, 0, 1, None) == -3
+    assert L.yoco_kv_cache_append(C.byref(d), p, p, p, 0, 9, None) == -2
+    # swa_decode
+    n, s = C.c_size_t(), C.c_int()
+    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(n), C.byref(s)) == 0
+    assert L.yoco_swa_decode(C.byref(d), p, p, p, 4, 1.0, p, n.value - 1, None) == -4
+    assert L.yoco_swa_decode(C.byref(d), p, p, p, 3, 1.0, p, n.value, None) == -1       # Hq % Hkv
+    assert L.yoco_swa_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
+    assert L.yoco_swa_decode(C.byref(d), p, p, p, 4, 1.0, p + 1, n.value, None) == -3

@@ -1,0 +1,208 @@
+"""Token-by-token generation through the self-decoder: the rolling window
+cache (ring writes, batched appends) bit-exactly against a numpy model of the
+slots, the one-token SWA decode step against the fp64 oracle's windowed
+definition, and a prefill + decode run of the whole stack against the oracle's
+all-at-once logits. Tolerances as in the other parity tests."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import yoco_synth as ys
+
+pytestmark = pytest.mark.gpu
+
+TD = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def yoco():
+    import paper_2405_05254_amd as y
+    y.lib()                       # fails loudly if libyoco.so is not built
+    assert torch.cuda.is_available()
+    return y
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda").to(TD[dtype])
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def check(got, ref, dtype, what):
+    st = ys.error_stats(got, ref)
+    tol = ys.TOL[dtype]
+    print("%s: max_abs %.3e mean_rel %.3e" % (what, st["max_abs"], st["mean_rel"]), flush=True)
+    assert np.isfinite(got).all(), what
+    assert st["max_abs"] <= tol["max_abs"] and st["mean_rel"] <= tol["mean_rel"], (what, st)
+
+
+# ------------------------------------------------------------ ring writes (exact)
+@pytest.mark.parametrize("dtype,src", [("bf16", "bf16"), ("f32", "f32"), ("bf16", "f32")])
+@pytest.mark.parametrize("C,pos0,n", [(16, 0, 7), (16, 5, 16), (16, 13, 9), (16, 3, 50), (100, 250, 333), (8, 8, 0)])
+def test_swa_cache_write_slots_are_exact(yoco, dtype, src, C, pos0, n):
+    """Row of position p lands in slot p mod C; with n > C only the last C rows
+    are kept; untouched slots keep their content."""
+    B, Hkv, d = 2, 3, 64
+    rng = np.random.default_rng(C * 1000 + pos0 + n)
+    ring = yoco.KVCache(B, Hkv, d, C, TD[dtype])
+    Kp, Vp = ring.planes()
+    Kp.fill_(-7.0)
+    Vp.fill_(-9.0)
+    k = ys.normal(rng, (n, Hkv, d), 1.0, src)
+    v = ys.normal(rng, (n, Hkv, d), 1.0, src)
+    yoco.swa_cache_write(ring, dev(k, src) if n else torch.empty(0, Hkv, d, device="cuda", dtype=TD[src]),
+                         dev(v, src) if n else torch.empty(0, Hkv, d, device="cuda", dtype=TD[src]), 1, pos0)
+    torch.cuda.synchronize()
+    wantK = np.full((B, Hkv, C, d), -7.0, dtype=np.float32)
+    wantV = np.full((B, Hkv, C, d), -9.0, dtype=np.float32)
+    for r in range(n):                                   # later rows overwrite earlier ones, as positions do
+        wantK[1, :, (pos0 + r) % C] = ys.round_to(k[r], dtype)
+        wantV[1, :, (pos0 + r) % C] = ys.round_to(v[r], dtype)
+    assert np.array_equal(Kp.float().cpu().numpy(), wantK)
+    assert np.array_equal(Vp.float().cpu().numpy(), wantV)
+
+
+@pytest.mark.parametrize("ring", [True, False])
+def test_kv_cache_append_batched_positions_are_exact(yoco, ring):
+    B, Hkv, d, N = 6, 2, 128, 40
+    rng = np.random.default_rng(5)
+    cache = yoco.KVCache(B, Hkv, d, N, torch.bfloat16)
+    Kp, Vp = cache.planes()
+    Kp.zero_()
+    Vp.zero_()
+    k = ys.normal(rng, (B, Hkv, d), 1.0, "bf16")
+    v = ys.normal(rng, (B, Hkv, d), 1.0, "bf16")
+    pos = np.array([0, 39, 40, 95, -1, 17], dtype=np.int64)      # 40 and 95 are beyond a plain cache; -1 is skipped
+    yoco.kv_cache_append(cache, dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(pos).cuda(), ring)
+    torch.cuda.synchronize()
+    wantK = np.zeros((B, Hkv, N, d), dtype=np.float32)
+    wantV = np.zeros((B, Hkv, N, d), dtype=np.float32)
+    for b, p in enumerate(pos):
+        if p < 0 or (p >= N and not ring):
+            continue
+        wantK[b, :, p % N] = k[b]
+        wantV[b, :, p % N] = v[b]
+    assert np.array_equal(Kp.float().cpu().numpy(), wantK)
+    assert np.array_equal(Vp.float().cpu().numpy(), wantV)
+
+
+# ------------------------------------------------- one-token SWA decode (Eq. 8)
+DECODE_CASES = [
+    # dtype, Hq, Hkv, d, C, lens (tokens so far, per sequence)
+    ("bf16", 24, 24, 128, 1024, [1, 700, 1024, 1025, 5000]),    # the self-decoder shape: before, at and after the wrap
+    ("bf16", 8, 2, 128, 300, [299, 300, 301, 1000]),            # GQA, window not a multiple of the kernel's chunk
+    ("bf16", 4, 4, 128, 1, [1, 9]),                             # window 1: o = v of the new row
+    ("f32", 4, 4, 64, 128, [5, 128, 129, 512]),                 # the tiny configuration (generic kernels)
+    ("f32", 6, 2, 32, 50, [50, 51, 149, 7]),
+]
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,C,lens", DECODE_CASES)
+def test_swa_decode_matches_oracle(yoco, dtype, Hq, Hkv, d, C, lens):
+    """History of each sequence written through the ring in two pieces (a bulk
+    write, then the last row by a batched append), one decode step, and the
+    oracle's Eq. 8 row over the full history."""
+    B, Tmax = len(lens), max(lens)
+    scale = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(len(lens) * 100 + C)
+    K = ys.normal(rng, (B, Tmax, Hkv, d), 1.0, dtype)
+    V = ys.normal(rng, (B, Tmax, Hkv, d), 1.0, dtype)
+    q = ys.normal(rng, (B, Hq, d), 1.0, dtype)
+    ring = yoco.KVCache(B, Hkv, d, C, TD[dtype])
+    for p_ in ring.planes():
+        p_.fill_(float("nan"))                       # a slot read without having been written poisons the output
+    for b, n in enumerate(lens):
+        if n > 1:
+            yoco.swa_cache_write(ring, dev(K[b, :n - 1], dtype), dev(V[b, :n - 1], dtype), b, 0)
+    last = np.stack([K[b, n - 1] for b, n in enumerate(lens)]), np.stack([V[b, n - 1] for b, n in enumerate(lens)])
+    ln = torch.tensor(lens, dtype=torch.int64, device="cuda")
+    yoco.kv_cache_append(ring, dev(last[0], dtype), dev(last[1], dtype), ln - 1, True)
+    nbytes, splits = yoco.cross_attn_decode_workspace(ring, Hq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    o = yoco.swa_decode(ring, dev(q, dtype), ln, scale, ws)
+    torch.cuda.synchronize()
+    got = host(o)
+    ref = np.empty_like(got)
+    for b, n in enumerate(lens):
+        Qb = np.zeros((n, Hq, d), dtype=np.float32)
+        Qb[n - 1] = q[b]
+        for h in range(Hq):
+            ref[b, h] = oracle.swa_row(Qb, K[b, :n], V[b, :n], n - 1, h, C, scale)
+    check(got, ref, dtype, "swa_decode C=%d lens=%s splits=%d" % (C, lens, splits))
+
+
+def test_swa_decode_token_by_token_through_several_wraps(yoco):
+    """Append + decode at every position of two sequences (one three positions
+    ahead of the other), against every row of the oracle's prefill definition."""
+    Hq, Hkv, d, C, T = 4, 2, 64, 16, 70
+    scale = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(9)
+    Q = ys.normal(rng, (2, T, Hq, d), 1.0, "f32")
+    K = ys.normal(rng, (2, T, Hkv, d), 1.0, "f32")
+    V = ys.normal(rng, (2, T, Hkv, d), 1.0, "f32")
+    ring = yoco.KVCache(2, Hkv, d, C, torch.float32)
+    nbytes, _ = yoco.cross_attn_decode_workspace(ring, Hq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    Qd, Kd, Vd = dev(Q, "f32"), dev(K, "f32"), dev(V, "f32")
+    got = np.zeros((2, T, Hq, d))
+    for t in range(T + 3):
+        pos_host = [t, t - 3]                           # sequence 1 starts three steps later (negative = skipped)
+        idx = [min(max(p, 0), T - 1) for p in pos_host]
+        pos = torch.tensor(pos_host, dtype=torch.int64, device="cuda")
+        k_t = torch.stack([Kd[b, idx[b]] for b in range(2)])
+        v_t = torch.stack([Vd[b, idx[b]] for b in range(2)])
+        q_t = torch.stack([Qd[b, idx[b]] for b in range(2)])
+        pos_w = torch.where(pos < T, pos, torch.full_like(pos, -1))      # finished sequences append nothing
+        yoco.kv_cache_append(ring, k_t.contiguous(), v_t.contiguous(), pos_w, True)
+        o = host(yoco.swa_decode(ring, q_t.contiguous(), torch.clamp(pos + 1, min=0), scale, ws))
+        for b in range(2):
+            if 0 <= pos_host[b] < T:
+                got[b, pos_host[b]] = o[b]
+    for b in range(2):
+        check(got[b], oracle.swa(Q[b], K[b], V[b], C, scale), "f32", "token-by-token sequence %d" % b)
+
+
+# ------------------------------------------------------ the stack, prompt + decode
+def test_tiny_stack_prefill_then_decode_matches_oracle(yoco):
+    """Tiny fp32 stack (window 128): early-exit prefill of 300 tokens, then 40
+    teacher-forced decode steps through the rolling caches and the global
+    cache; every step's logits against the oracle's all-at-once forward."""
+    from paper_2405_05254_amd.stack import YocoStack
+    c = ys.CONFIGS["tiny_fp32"]
+    w = ys.stack_weights(c["seed"], c["stack"], "f32")
+    T0, steps = 300, 40
+    tok = ys.tokens(c["seed"] + 1, T0 + steps, c["stack"]["vocab"])
+    ref = oracle.yoco_stack(tok, w, "full")
+    st = YocoStack(w, torch.float32)
+    t = torch.from_numpy(tok).cuda()
+    state = st.new_generation_state(T0 + steps)
+    logits = [host(st.prefill(t[:T0], state))[0]]
+    for i in range(steps):
+        logits.append(host(st.decode_step(t[T0 + i], state))[0])
+    got = np.stack(logits)
+    err = np.abs(got - ref[T0 - 1:]).max()
+    print("prefill + %d decode steps vs oracle: %.3e" % (steps, err), flush=True)
+    assert err <= 1e-3
+    assert state["length"] == T0 + steps
+
+
+def test_tiny_stack_generation_from_an_empty_state_matches_oracle(yoco):
+    """No prompt: 150 decode steps from position 0 (the rings wrap at 128)."""
+    from paper_2405_05254_amd.stack import YocoStack
+    c = ys.CONFIGS["tiny_fp32"]
+    w = ys.stack_weights(c["seed"], c["stack"], "f32")
+    T = 150
+    tok = ys.tokens(c["seed"] + 2, T, c["stack"]["vocab"])
+    ref = oracle.yoco_stack(tok, w, "full")
+    st = YocoStack(w, torch.float32)
+    t = torch.from_numpy(tok).cuda()
+    state = st.new_generation_state(T)
+    got = np.stack([host(st.decode_step(t[i], state))[0] for i in range(T)])
+    err = np.abs(got - ref).max()
+    print("150 decode steps from an empty state vs oracle: %.3e" % err, flush=True)
+    assert err <= 1e-3
