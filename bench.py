@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes of one SWA prefill launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) of `bench.py --only swa`, each scaled by what the counter reads for a 1 GiB copy (`--only calib`:
 # FETCH_SIZE reads 0.5 GiB -> factor 2.0, WRITE_SIZE reads 1.0 GiB -> factor 1.0). See profiles/.
-SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 304680.7 * 1024, "write": 1.0 * 197950.2 * 1024}
+SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308131.2 * 1024, "write": 1.0 * 198398.8 * 1024}
 
 
 def swa_flops(T, H, d, C):
@@ -164,7 +164,7 @@ def main():
             for pl in r.planes():
                 pl.copy_(ys.device_normal(pl.shape, 300 + i, 1.0, torch.bfloat16, dev))
         qs = [ys.device_normal((B, Hs, d), 400 + i, 1.0, torch.bfloat16, dev) for i in range(layers)]
-        kn = ys.device_normal((B, Hs, d), 500, 1.0, torch.bfloat16, dev)
+        k_new = ys.device_normal((B, Hs, d), 500, 1.0, torch.bfloat16, dev)
         od = torch.empty_like(qs[0])
         pos = torch.full((B,), 32767, dtype=torch.int64, device=dev)
         ln = pos + 1
@@ -175,7 +175,7 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for i in range(layers):
-                yoco.kv_cache_append(rings[i], kn, kn, pos, True)
+                yoco.kv_cache_append(rings[i], k_new, k_new, pos, True)
                 yoco.swa_decode(rings[i], qs[i], ln, scale, w, out=od)
             e1.record()
             torch.cuda.synchronize()
@@ -221,7 +221,7 @@ def main():
         "roofline": {"kernel": "yoco_swa_prefill", "bound": "mfma", "achieved": round(swa_tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": int(SWA_TRAFFIC_BYTES["fetch"] + SWA_TRAFFIC_BYTES["write"]),
-                     "traffic_note": "HBM bytes per launch (fetch 0.624 GB + write 0.203 GB) against 0.805 GB algorithmic"},
+                     "traffic_note": "HBM bytes per launch (fetch 0.631 GB + write 0.203 GB) against 0.805 GB algorithmic"},
         "decode": decode,
         "cpu_baseline": cpu,
     }
