@@ -14,6 +14,12 @@ prefix invariants of the stack, and the paper's cache-size arithmetic
 The rolling-window cache and the token-by-token stack are pinned to the
 windowed definition (a literal-mask brute force over the full history) and to
 the all-at-once stack, whose outputs an autoregressive model must reproduce.
+Gated retention (Eq. 4-7): the parallel form is the definition written out
+(products of the decays); it is pinned by a brute-force triple loop, by the
+paper's own statement that the parallel, recurrent and chunkwise forms give the
+same result (also across a split of the sequence with a carried state), by
+the closed forms gamma = 1 (causal prefix sums) and gamma -> 0 (only the
+diagonal term), and GroupNorm by torch's group_norm.
 No function here is "parity unpinned".
 
 Readings of points the paper leaves open (all listed in the design doc):
@@ -222,6 +228,98 @@ def yoco_stack_generate(tokens, w):
             x = swiglu(rmsnorm(y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + y
         out.append((rmsnorm(x, w["final_ln"], eps) @ np.asarray(w["W_out"], F64))[0])
     return np.stack(out)
+
+
+# ---------------------------------------------------------------- gated retention
+def gret_decay(X, W_gamma, tau):
+    """gamma = sigmoid(X W_gamma)^(1/tau) (section 3.1, Eq. 4): one decay in (0, 1)
+    per token and head. X [T,dm], W_gamma [dm,H] -> gamma [T,H]."""
+    z = np.asarray(X, dtype=F64) @ np.asarray(W_gamma, dtype=F64)
+    return (1.0 / (1.0 + np.exp(-z))) ** (1.0 / tau)
+
+
+def gret_parallel(Q, K, V, gamma, scale):
+    """Parallel form of gated retention (Eq. 4): (Q K^T * D) V per head with
+    D_nm = prod_{i=m+1..n} gamma_i for n >= m (1 on the diagonal) and 0 above.
+    Q, K [T,H,dk]; V [T,H,dv]; gamma [T,H] -> [T,H,dv]. `scale` multiplies
+    Q K^T (the equation prints none; it cancels in the GroupNorm of Eq. 7)."""
+    T, H, _ = Q.shape
+    Q, K, V, gamma = (np.asarray(a, dtype=F64) for a in (Q, K, V, gamma))
+    O = np.zeros((T, H, V.shape[2]), dtype=F64)
+    for h in range(H):
+        D = np.zeros((T, T), dtype=F64)
+        for n in range(T):
+            for m in range(n + 1):
+                D[n, m] = np.prod(gamma[m + 1:n + 1, h])
+        O[:, h] = (scale * (Q[:, h] @ K[:, h].T) * D) @ V[:, h]
+    return O
+
+
+def gret_recurrent(Q, K, V, gamma, scale, S0=None):
+    """Recurrent form (Eq. 5): S_n = gamma_n S_{n-1} + K_n^T V_n, o_n = Q_n S_n.
+    S0 [H,dk,dv] is the state before the first row (zeros if None).
+    Returns (O [T,H,dv], S_T [H,dk,dv])."""
+    T, H, dk = Q.shape
+    dv = V.shape[2]
+    Q, K, V, gamma = (np.asarray(a, dtype=F64) for a in (Q, K, V, gamma))
+    S = np.zeros((H, dk, dv), dtype=F64) if S0 is None else np.array(S0, dtype=F64)
+    O = np.zeros((T, H, dv), dtype=F64)
+    for n in range(T):
+        for h in range(H):
+            S[h] = gamma[n, h] * S[h] + np.outer(K[n, h], V[n, h])
+            O[n, h] = scale * (Q[n, h] @ S[h])
+    return O, S
+
+
+def gret_chunkwise(Q, K, V, gamma, scale, chunk, S0=None):
+    """Chunkwise recurrent form (Eq. 6, appendix B). Within chunk [i], with
+    beta_j the product of the chunk's decays up to and including row j:
+      inner  = (Q K^T * D) V,  D(j,k) = beta_j / beta_k for k <= j, else 0
+      cross  = (Q R_{i-1}) * beta_j                      (row-wise)
+      R_i    = K^T (V * beta_last / beta_j) + beta_last R_{i-1}
+    (Eq. 6 prints D(j,k) with j and k exchanged; the proof in appendix B and
+    Eq. 4 fix the reading used here.) The last chunk may be shorter.
+    Returns (O [T,H,dv], R_last [H,dk,dv])."""
+    T, H, dk = Q.shape
+    dv = V.shape[2]
+    Q, K, V, gamma = (np.asarray(a, dtype=F64) for a in (Q, K, V, gamma))
+    R = np.zeros((H, dk, dv), dtype=F64) if S0 is None else np.array(S0, dtype=F64)
+    O = np.zeros((T, H, dv), dtype=F64)
+    for c0 in range(0, T, chunk):
+        c1 = min(T, c0 + chunk)
+        for h in range(H):
+            beta = np.cumprod(gamma[c0:c1, h])
+            q, k, v = Q[c0:c1, h], K[c0:c1, h], V[c0:c1, h]
+            D = np.tril(beta[:, None] / beta[None, :])
+            inner = (scale * (q @ k.T) * D) @ v
+            cross = scale * (q @ R[h]) * beta[:, None]
+            O[c0:c1, h] = inner + cross
+            R[h] = k.T @ (v * (beta[-1] / beta)[:, None]) + beta[-1] * R[h]
+    return O, R
+
+
+def group_norm_heads(O, eps=1e-6):
+    """GroupNorm_h of Eq. 7 with one group per head and no learned affine:
+    every head's dv-vector is shifted to zero mean and scaled to unit variance
+    (biased variance, eps inside the root). O [..., H, dv]."""
+    O = np.asarray(O, dtype=F64)
+    mu = O.mean(axis=-1, keepdims=True)
+    var = ((O - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (O - mu) / np.sqrt(var + eps)
+
+
+def mhgr(X, W_Q, W_K, W_V, W_gamma, W_G, W_O, H, tau, scale, eps=1e-6):
+    """Multi-head gated retention (Eq. 7): (swish(X W_G) * GroupNorm_h(heads)) W_O
+    with head_i = gRet(X) in its parallel form; no rotation Theta (the
+    configurations use no positional encoding). X [T,dm] -> [T,dm]."""
+    X = np.asarray(X, dtype=F64)
+    T = X.shape[0]
+    Q = (X @ np.asarray(W_Q, F64)).reshape(T, H, -1)
+    K = (X @ np.asarray(W_K, F64)).reshape(T, H, -1)
+    V = (X @ np.asarray(W_V, F64)).reshape(T, H, -1)
+    Y = group_norm_heads(gret_parallel(Q, K, V, gret_decay(X, W_gamma, tau), scale), eps).reshape(T, -1)
+    a = X @ np.asarray(W_G, F64)
+    return ((a / (1.0 + np.exp(-a))) * Y) @ np.asarray(W_O, F64)
 
 
 def kv_cache_bytes_per_token(Hkv, d, elem_bytes, cached_layers=1):

@@ -128,3 +128,93 @@ RING_MUTANTS = {
 @pytest.mark.parametrize("name", sorted(RING_MUTANTS))
 def test_pins_catch_planted_ring_mistake(name):
     assert not battery(make_ring_attention(**RING_MUTANTS[name])), name
+
+
+# ---- gated retention: planted mistakes in copies of the recurrent and chunkwise forms
+def make_gret(first=lambda m: m + 1, decay_after_add=False, d_transposed=False, cross_decay=True, value_decay=True,
+              carry_decay=True, chunk=5):
+    """Returns (parallel, recurrent, chunkwise) copies with switches for planted mistakes."""
+    def parallel(Q, K, V, gamma, scale):
+        T, H, _ = Q.shape
+        O = np.zeros((T, H, V.shape[2]))
+        for h in range(H):
+            D = np.zeros((T, T))
+            for n in range(T):
+                for m in range(n + 1):
+                    D[n, m] = np.prod(gamma[first(m):n + 1, h])
+            O[:, h] = (scale * (Q[:, h] @ K[:, h].T) * D) @ V[:, h]
+        return O
+
+    def recurrent(Q, K, V, gamma, scale):
+        T, H, dk = Q.shape
+        S = np.zeros((H, dk, V.shape[2]))
+        O = np.zeros((T, H, V.shape[2]))
+        for n in range(T):
+            for h in range(H):
+                kv = np.outer(K[n, h], V[n, h])
+                S[h] = gamma[n, h] * (S[h] + kv) if decay_after_add else gamma[n, h] * S[h] + kv
+                O[n, h] = scale * (Q[n, h] @ S[h])
+        return O
+
+    def chunkwise(Q, K, V, gamma, scale):
+        T, H, dk = Q.shape
+        R = np.zeros((H, dk, V.shape[2]))
+        O = np.zeros((T, H, V.shape[2]))
+        for c0 in range(0, T, chunk):
+            c1 = min(T, c0 + chunk)
+            for h in range(H):
+                beta = np.cumprod(gamma[c0:c1, h])
+                q, k, v = Q[c0:c1, h], K[c0:c1, h], V[c0:c1, h]
+                D = np.tril(beta[None, :] / beta[:, None]) if d_transposed else np.tril(beta[:, None] / beta[None, :])
+                O[c0:c1, h] = (scale * (q @ k.T) * D) @ v + scale * (q @ R[h]) * (beta[:, None] if cross_decay else 1.0)
+                vd = v * (beta[-1] / beta)[:, None] if value_decay else v
+                R[h] = k.T @ vd + (beta[-1] if carry_decay else 1.0) * R[h]
+        return O
+    return parallel, recurrent, chunkwise
+
+
+def gret_battery(fn):
+    """True if `fn(Q, K, V, gamma, scale)` passes the pins: scalar-loop brute force, gamma = 1 prefix sums."""
+    rng = np.random.default_rng(3)
+    T, H = 13, 2
+    Q, K, V = rng.standard_normal((T, H, 4)), rng.standard_normal((T, H, 4)), rng.standard_normal((T, H, 3))
+    gamma = 0.5 + 0.5 * rng.random((T, H))
+    ref = np.zeros((T, H, 3))
+    for h in range(H):
+        for n in range(T):
+            for m in range(n + 1):
+                decay = 1.0
+                for i in range(m + 1, n + 1):
+                    decay *= gamma[i, h]
+                ref[n, h] += 0.7 * decay * (Q[n, h] @ K[m, h]) * V[m, h]
+    if np.abs(fn(Q, K, V, gamma, 0.7) - ref).max() > 1e-11:
+        return False
+    ones = np.ones((T, H))
+    pre = np.stack([np.stack([Q[n, h] @ (K[:n + 1, h].T @ V[:n + 1, h]) for h in range(H)]) for n in range(T)])
+    return np.abs(fn(Q, K, V, ones, 1.0) - pre).max() < 1e-11
+
+
+def test_the_unmutated_gret_copies_and_the_oracle_pass():
+    for fn in make_gret():
+        assert gret_battery(fn)
+    assert gret_battery(oracle.gret_parallel)
+    assert gret_battery(lambda *a: oracle.gret_recurrent(*a)[0])
+    assert gret_battery(lambda Q, K, V, g, s: oracle.gret_chunkwise(Q, K, V, g, s, 5)[0])
+    assert gret_battery(lambda Q, K, V, g, s: oracle.gret_chunkwise(Q, K, V, g, s, 64)[0])
+
+
+GRET_MUTANTS = {
+    "decay product starts one row early": (0, dict(first=lambda m: m)),
+    "decay product starts one row late": (0, dict(first=lambda m: m + 2)),
+    "state decayed after the new term is added": (1, dict(decay_after_add=True)),
+    "inner-chunk decay matrix with rows and columns exchanged (as Eq. 6 prints it)": (2, dict(d_transposed=True)),
+    "cross-chunk term without its row decay": (2, dict(cross_decay=False)),
+    "chunk state without the value decay": (2, dict(value_decay=False)),
+    "chunk state carried without the chunk's total decay": (2, dict(carry_decay=False)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(GRET_MUTANTS))
+def test_pins_catch_planted_gret_mistake(name):
+    which, kw = GRET_MUTANTS[name]
+    assert not gret_battery(make_gret(**kw)[which]), name

@@ -348,3 +348,118 @@ def test_bf16_rounding_is_rne_and_idempotent():
     assert np.array_equal(ys.round_to(r, "bf16"), r)
     big = np.random.default_rng(0).standard_normal(100000).astype(np.float32)
     assert np.array_equal(ys.round_to(big, "bf16"), torch.from_numpy(big).to(torch.bfloat16).float().numpy())
+
+
+# ------------------------------------------------ gated retention (Eq. 4-7)
+def rand_gret(seed, T, H, dk, dv, lo=0.6):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, H, dk)), rng.standard_normal((T, H, dk)), rng.standard_normal((T, H, dv)),
+            lo + (1.0 - lo) * rng.random((T, H)))
+
+
+def gret_brute_force(Q, K, V, gamma, scale):
+    """o_n = sum_{m<=n} (prod_{i=m+1..n} gamma_i) (q_n . k_m) v_m with scalar loops."""
+    T, H, dk = Q.shape
+    O = np.zeros((T, H, V.shape[2]))
+    for h in range(H):
+        for n in range(T):
+            for m in range(n + 1):
+                decay = 1.0
+                for i in range(m + 1, n + 1):
+                    decay *= gamma[i, h]
+                dot = sum(Q[n, h, e] * K[m, h, e] for e in range(dk))
+                O[n, h] += scale * decay * dot * V[m, h]
+    return O
+
+
+def test_gret_parallel_matches_brute_force():
+    Q, K, V, gamma = rand_gret(21, 11, 2, 4, 3)
+    assert np.abs(oracle.gret_parallel(Q, K, V, gamma, 0.7) - gret_brute_force(Q, K, V, gamma, 0.7)).max() < 1e-12
+
+
+@pytest.mark.parametrize("chunk", [1, 4, 7, 16, 64])
+def test_gret_three_forms_agree(chunk):
+    """Section 3.1: the parallel, recurrent and chunkwise forms are equivalent
+    (appendix B); the last chunk is ragged for chunk = 7 and 16."""
+    Q, K, V, gamma = rand_gret(22, 37, 3, 8, 6)
+    par = oracle.gret_parallel(Q, K, V, gamma, 0.3)
+    rec, S = oracle.gret_recurrent(Q, K, V, gamma, 0.3)
+    chk, R = oracle.gret_chunkwise(Q, K, V, gamma, 0.3, chunk)
+    assert np.abs(rec - par).max() < 1e-11
+    assert np.abs(chk - par).max() < 1e-11
+    assert np.abs(R - S).max() < 1e-11
+
+
+def test_gret_state_carries_across_a_split():
+    """Processing rows [0, 20) and then [20, 37) with the carried state equals one pass."""
+    Q, K, V, gamma = rand_gret(23, 37, 2, 8, 8)
+    full = oracle.gret_parallel(Q, K, V, gamma, 1.0)
+    o1, S1 = oracle.gret_chunkwise(Q[:20], K[:20], V[:20], gamma[:20], 1.0, 8)
+    o2, S2 = oracle.gret_chunkwise(Q[20:], K[20:], V[20:], gamma[20:], 1.0, 8, S0=S1)
+    o3, S3 = oracle.gret_recurrent(Q[20:], K[20:], V[20:], gamma[20:], 1.0, S0=S1)
+    assert np.abs(np.concatenate([o1, o2]) - full).max() < 1e-11
+    assert np.abs(o3 - o2).max() < 1e-11 and np.abs(S3 - S2).max() < 1e-11
+
+
+def test_gret_closed_forms():
+    Q, K, V, _ = rand_gret(24, 15, 2, 4, 4)
+    T = Q.shape[0]
+    # gamma = 1: plain causal linear attention, o_n = q_n . sum_{m<=n} k_m^T v_m
+    ones = np.ones((T, 2))
+    ref = np.zeros_like(V)
+    for h in range(2):
+        S = np.zeros((4, 4))
+        for n in range(T):
+            S += np.outer(K[n, h], V[n, h])
+            ref[n, h] = Q[n, h] @ S
+    assert np.abs(oracle.gret_parallel(Q, K, V, ones, 1.0) - ref).max() < 1e-12
+    # gamma = 0: only the diagonal term survives (the empty product is 1)
+    diag = np.einsum("the,the->th", Q, K)[..., None] * V
+    for fn in (lambda: oracle.gret_parallel(Q, K, V, 0 * ones, 1.0), lambda: oracle.gret_recurrent(Q, K, V, 0 * ones, 1.0)[0]):
+        assert np.abs(fn() - diag).max() < 1e-12
+    # a constant decay g: D_nm = g^(n-m) (retention with a fixed decay)
+    g = 0.9
+    D = np.tril(g ** (np.arange(T)[:, None] - np.arange(T)[None, :]).clip(0))
+    ref = np.stack([(Q[:, h] @ K[:, h].T * D) @ V[:, h] for h in range(2)], axis=1)
+    assert np.abs(oracle.gret_parallel(Q, K, V, g * ones, 1.0) - ref).max() < 1e-12
+
+
+def test_gret_is_causal_and_scale_is_linear():
+    Q, K, V, gamma = rand_gret(25, 12, 1, 4, 4)
+    base = oracle.gret_parallel(Q, K, V, gamma, 1.0)
+    K2, V2, g2 = K.copy(), V.copy(), gamma.copy()
+    K2[8:] += 1.0
+    V2[8:] -= 1.0
+    g2[8:] *= 0.5
+    assert np.array_equal(oracle.gret_parallel(Q, K2, V2, g2, 1.0)[:8], base[:8])
+    assert np.abs(oracle.gret_parallel(Q, K, V, gamma, 0.25) - 0.25 * base).max() < 1e-13
+
+
+def test_gret_decay_and_group_norm_against_library():
+    rng = np.random.default_rng(26)
+    X, W = rng.standard_normal((9, 16)), rng.standard_normal((16, 3))
+    ref = torch.exp(F.logsigmoid(torch.from_numpy(X @ W)) / 16.0).numpy()       # sigmoid(z)^(1/tau)
+    got = oracle.gret_decay(X, W, 16.0)
+    assert np.abs(got - ref).max() < 1e-14 and (got > 0).all() and (got < 1).all()
+    O = rng.standard_normal((9, 3, 8)) * 3 + 1
+    ref = F.group_norm(torch.from_numpy(O.reshape(9, 24)), 3, eps=1e-6).numpy().reshape(9, 3, 8)
+    assert np.abs(oracle.group_norm_heads(O, 1e-6) - ref).max() < 1e-12
+
+
+def test_mhgr_matches_library_composition():
+    """Eq. 7 assembled from torch ops (cumulative log-decays, masked product,
+    group_norm, silu) against the oracle."""
+    rng = np.random.default_rng(27)
+    T, dm, H, dh, tau = 14, 16, 2, 8, 16.0
+    X = rng.standard_normal((T, dm))
+    Ws = {n: rng.standard_normal((dm, dm)) * 0.3 for n in ("W_Q", "W_K", "W_V", "W_G", "W_O")}
+    Wg = rng.standard_normal((dm, H))
+    got = oracle.mhgr(X, Ws["W_Q"], Ws["W_K"], Ws["W_V"], Wg, Ws["W_G"], Ws["W_O"], H, tau, 0.5)
+    x = torch.from_numpy(X)
+    q, k, v = ((x @ torch.from_numpy(Ws[n])).view(T, H, dh).transpose(0, 1) for n in ("W_Q", "W_K", "W_V"))
+    G = (F.logsigmoid(x @ torch.from_numpy(Wg)) / tau).cumsum(0).transpose(0, 1)          # [H,T]
+    mask = (G[:, :, None] - G[:, None, :] + torch.full((T, T), float("-inf"), dtype=torch.float64).triu(1)).exp()
+    heads = ((0.5 * q @ k.transpose(1, 2)) * mask) @ v                                     # [H,T,dh]
+    y = F.group_norm(heads.transpose(0, 1).reshape(T, H * dh), H, eps=1e-6)
+    ref = ((F.silu(x @ torch.from_numpy(Ws["W_G"])) * y) @ torch.from_numpy(Ws["W_O"])).numpy()
+    assert np.abs(got - ref).max() < 1e-10
