@@ -15,6 +15,9 @@
  *                             token-by-token generation: the self-decoder's
  *                             rolling window cache (section 3.2) and batched
  *                             one-row appends
+ *   yoco_gret_prefill, yoco_gret_decode
+ *                             gated retention (section 3.1, Eq. 4-7), chunkwise
+ *                             for prompts and recurrent for generation
  *
  * Conventions
  *   - Every pointer named q/k/v/o/lens/workspace/mem is DEVICE memory owned by
@@ -183,6 +186,48 @@ int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, c
  */
 int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int64_t* lens, int Hq, float scale,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Gated retention, the paper's other self-decoder module (section 3.1) ----
+ * Per head, with decays gamma_n in (0, 1] given as log_gamma[b,n,h] = ln gamma_n
+ * (fp32; Eq. 4: gamma = sigmoid(X W_gamma)^(1/tau), computed by the caller):
+ *   o_n = scale * sum_{m <= n} (prod_{i=m+1..n} gamma_i) (q_n . k_m) v_m      (Eq. 4)
+ * which equals the recurrence S_n = gamma_n S_{n-1} + k_n^T v_n, o_n = scale * q_n S_n
+ * (Eq. 5) and the chunkwise form of Eq. 6. q, k: [B,T,H,dk]; v, o: [B,T,H,dv],
+ * all of `dtype`. Eq. 4 prints no scale; any value cancels in the GroupNorm.
+ * The rotation Theta of Eq. 4 is the caller's (q and k arrive rotated, or not).
+ * group_norm != 0 applies Eq. 7's GroupNorm_h to every head's dv-vector before
+ * it is stored: (o - mean) / sqrt(var + eps), no learned affine; the swish gate
+ * and W_O of Eq. 7 are the caller's.
+ * States are fp32 [B,H,dv,dk]: element (e_v, e_k) is S[e_k][e_v] of Eq. 5, i.e.
+ * S is stored transposed so that its rows run along the key dimension.
+ * state_in: the state before row 0 (NULL = zeros); state_out: receives the
+ * state after the last row (NULL = not stored); they may be the same memory.
+ */
+
+/* Scratch bytes yoco_gret_prefill needs for its chunkwise path on this shape
+ * (0 when the shape has no such path and the recurrent kernel serves it). Host only. */
+int yoco_gret_prefill_workspace(int B, int64_t T, int H, int dk, int dv, int chunk, int dtype, size_t* bytes);
+
+/*
+ * Gated retention over T rows per sequence (prefill; Eq. 6 with chunk size
+ * `chunk`, the paper uses 256). bf16 with dk = dv = 128 and chunk a multiple
+ * of 128 runs chunkwise on the matrix cores when `workspace` holds at least
+ * yoco_gret_prefill_workspace() bytes (device memory, 256-byte aligned); every
+ * other case runs the recurrence, which computes the same function (dk, dv <=
+ * 128). T == 0 copies state_in to state_out.
+ */
+int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, void* o,
+                      const float* state_in, float* state_out, int B, int64_t T, int H, int dk, int dv, int chunk,
+                      float scale, int group_norm, float eps, int dtype, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * One generation step (Eq. 5) for one new row per sequence: q, k: [B,H,dk];
+ * v, o: [B,H,dv]; log_gamma: [B,H]; state: [B,H,dv,dk] fp32, updated in place.
+ */
+int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, void* o, float* state,
+                     int B, int H, int dk, int dv, float scale, int group_norm, float eps, int dtype, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). */
 const char* yoco_last_error_string(void);

@@ -88,6 +88,15 @@ int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* le
   return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, c.dtype, s), what);
 }
 
+int check_gret_shape(int B, int64_t T, int H, int dk, int dv, int dtype) {
+  if (B <= 0 || H <= 0 || T < 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive B or H, or negative T");
+  if (B > 65535 || H > 65535) return fail(YOCO_ERR_UNSUPPORTED, "B %d or H %d exceeds the grid limit", B, H);
+  if (!dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (dk <= 0 || dv <= 0 || dk > 256 || dv > 256) return fail(YOCO_ERR_UNSUPPORTED, "head dims %d, %d not in [8, 256]", dk, dv);
+  if (dk % 8 || dv % 8) return fail(YOCO_ERR_ALIGNMENT, "head dims %d, %d are not multiples of 8", dk, dv);
+  return YOCO_OK;
+}
+
 constexpr int64_t kFewRows = 8;   // query rows up to which the prefill call splits over the cache like decode
 
 }  // namespace
@@ -295,6 +304,66 @@ int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int
   if (rc) return rc;
   if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
   return run_decode(*ring, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "swa_decode");
+}
+
+int yoco_gret_prefill_workspace(int B, int64_t T, int H, int dk, int dv, int chunk, int dtype, size_t* bytes) {
+  if (!bytes) return fail(YOCO_ERR_INVALID_ARG, "bytes is null");
+  int rc = check_gret_shape(B, T, H, dk, dv, dtype);
+  if (rc) return rc;
+  if (chunk <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive chunk");
+  *bytes = yoco::gret_chunk_supported(B, T, H, dk, dv, chunk, dtype) ? yoco::gret_chunk_workspace(B, T, H, chunk) : 0;
+  return YOCO_OK;
+}
+
+int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, void* o,
+                      const float* state_in, float* state_out, int B, int64_t T, int H, int dk, int dv, int chunk,
+                      float scale, int group_norm, float eps, int dtype, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  int rc = check_gret_shape(B, T, H, dk, dv, dtype);
+  if (rc) return rc;
+  if (chunk <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive chunk");
+  if (!(eps >= 0.f)) return fail(YOCO_ERR_INVALID_ARG, "negative eps");
+  if (state_in && !aligned16(state_in)) return fail(YOCO_ERR_ALIGNMENT, "state_in not 16-byte aligned");
+  if (state_out && !aligned16(state_out)) return fail(YOCO_ERR_ALIGNMENT, "state_out not 16-byte aligned");
+  if (workspace && (((uintptr_t)workspace) & 255u)) return fail(YOCO_ERR_ALIGNMENT, "workspace not 256-byte aligned");
+  if (T == 0) {
+    if (!state_out || state_out == state_in) return YOCO_OK;
+    const size_t nb = (size_t)B * H * dk * dv * sizeof(float);
+    if (state_in) return hip_result(hipMemcpyAsync(state_out, state_in, nb, hipMemcpyDeviceToDevice, (hipStream_t)stream), "gret_prefill");
+    return hip_result(yoco::launch_fill_zero(state_out, nb / sizeof(float), (hipStream_t)stream), "gret_prefill");
+  }
+  if (!q || !k || !v || !log_gamma || !o) return fail(YOCO_ERR_INVALID_ARG, "null tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (((uintptr_t)log_gamma) & 3u))
+    return fail(YOCO_ERR_ALIGNMENT, "tensor pointer not aligned");
+  yoco::GretView a;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma;
+  a.state_in = state_in; a.state_out = state_out;
+  a.T = T; a.B = B; a.H = H; a.dk = dk; a.dv = dv;
+  a.scale = scale; a.eps = eps; a.group_norm = group_norm != 0;
+  if (workspace && yoco::gret_chunk_supported(B, T, H, dk, dv, chunk, dtype) &&
+      workspace_bytes >= yoco::gret_chunk_workspace(B, T, H, chunk))
+    return hip_result(yoco::launch_gret_chunk(a, chunk, workspace, (hipStream_t)stream), "gret_prefill (chunkwise)");
+  if (!yoco::gret_recurrent_supported(a))
+    return fail(YOCO_ERR_UNSUPPORTED, "gated retention: dk %d, dv %d have no kernel (at most 128)", dk, dv);
+  return hip_result(yoco::launch_gret_recurrent(a, dtype, (hipStream_t)stream), "gret_prefill");
+}
+
+int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, void* o, float* state,
+                     int B, int H, int dk, int dv, float scale, int group_norm, float eps, int dtype, void* stream) {
+  int rc = check_gret_shape(B, 1, H, dk, dv, dtype);
+  if (rc) return rc;
+  if (!(eps >= 0.f)) return fail(YOCO_ERR_INVALID_ARG, "negative eps");
+  if (!q || !k || !v || !log_gamma || !o || !state) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(state) || (((uintptr_t)log_gamma) & 3u))
+    return fail(YOCO_ERR_ALIGNMENT, "pointer not aligned");
+  yoco::GretView a;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma;
+  a.state_in = state; a.state_out = state;
+  a.T = 1; a.B = B; a.H = H; a.dk = dk; a.dv = dv;
+  a.scale = scale; a.eps = eps; a.group_norm = group_norm != 0;
+  if (!yoco::gret_recurrent_supported(a))
+    return fail(YOCO_ERR_UNSUPPORTED, "gated retention: dk %d, dv %d have no kernel (at most 128)", dk, dv);
+  return hip_result(yoco::launch_gret_recurrent(a, dtype, (hipStream_t)stream), "gret_decode");
 }
 
 }  // extern "C"

@@ -44,6 +44,23 @@ struct AttnView {
   float scale;
 };
 
+// One gated-retention problem (section 3.1). q, k: [B,T,H,dk]; v, o: [B,T,H,dv];
+// log_gamma: [B,T,H] fp32, the natural log of the decays; states: [B,H,dv,dk]
+// fp32 (the transpose of S = K^T V), either may be null.
+struct GretView {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* o;
+  const float* log_gamma;
+  const float* state_in;
+  float* state_out;
+  int64_t T;
+  int B, H, dk, dv;
+  float scale, eps;
+  int group_norm;
+};
+
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_attn_generic(const AttnView& a, int dtype, hipStream_t s);
 hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq,
@@ -54,6 +71,14 @@ hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v,
                            int64_t n, int src_dtype, hipStream_t s);
 hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int ring,
                             int src_dtype, hipStream_t s);
+
+bool gret_recurrent_supported(const GretView& a);
+hipError_t launch_gret_recurrent(const GretView& a, int dtype, hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+// Chunkwise form on the matrix cores (bf16, dk = dv = 128).
+bool gret_chunk_supported(int B, int64_t T, int H, int dk, int dv, int chunk, int dtype);
+size_t gret_chunk_workspace(int B, int64_t T, int H, int chunk);
+hipError_t launch_gret_chunk(const GretView& a, int chunk, void* workspace, hipStream_t s);
 
 // bf16, d = 128 fast paths. `supported` functions are host-side predicates.
 bool swa_mfma_supported(const AttnView& a, int dtype);

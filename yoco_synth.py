@@ -68,6 +68,18 @@ def qkv(seed, T, Hq, Hkv, d, std, dtype):
             normal(rng, (T, Hkv, d), std, dtype))
 
 
+def gret_inputs(seed, B, T, H, dk, dv, std, dtype, mean_log_decay=0.04):
+    """Inputs of gated retention: q, k [B,T,H,dk], v [B,T,H,dv] as for attention, and the log-decays
+    ln(gamma) [B,T,H] in float32, drawn as minus an exponential variate (gamma in (0, 1), mostly 0.9-1:
+    the range a sigmoid raised to 1/16 produces)."""
+    rng = np.random.default_rng(seed)
+    q = normal(rng, (B, T, H, dk), std, dtype)
+    k = normal(rng, (B, T, H, dk), std, dtype)
+    v = normal(rng, (B, T, H, dv), std, dtype)
+    lg = (-rng.exponential(mean_log_decay, size=(B, T, H))).astype(np.float32)
+    return q, k, v, lg
+
+
 def stack_weights(seed, s, dtype):
     """Random-init YOCO stack: matrices ~ N(0, 0.02), RMSNorm gains 1, no bias."""
     rng = np.random.default_rng(seed)
