@@ -28,6 +28,7 @@
 // bank-conflict free.
 #include <type_traits>
 
+#include "mfma_util.h"
 #include "yoco_common.h"
 
 namespace yoco {
@@ -49,40 +50,6 @@ constexpr int kTileBytes = kBN * kD * 2;     // 16 KiB
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazyLog2 = 8.0f;            // rescale only when the max grows by more than 2^8
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) char lds_char;
-
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-
-// Two fp32 -> packed fp16, round to nearest even.
-__device__ __forceinline__ unsigned pack_f16(float a, float b) {
-  f32x2 v = {a, b};
-  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, f16x2));
-}
-// Two packed bf16 -> two packed fp16. Exact for magnitudes in [2^-14, 65504]
-// (bf16 carries 8 significant bits, fp16 11); smaller ones lose low bits or
-// flush (absolute error below 2^-25), larger ones overflow.
-__device__ __forceinline__ unsigned bf16x2_to_f16x2(unsigned x) {
-  return pack_f16(__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u));
-}
-
-__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
-  f32x2 v = {a, b};
-  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
-}
-
-__device__ __forceinline__ float other_half(float x) {        // value held by lane ^ 32
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
-}
 
 struct Args {
   AttnView a;

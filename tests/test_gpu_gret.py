@@ -3,7 +3,9 @@ oracle: the recurrent kernel (prefill of the shapes without a chunkwise path,
 and the decode step), the chunkwise MFMA path, carried states, and the fused
 GroupNorm. Tolerances: fp32 1e-4; bf16 max-abs 2e-2 and sum-ratio 2e-3 on
 GroupNorm'ed outputs (unit variance); raw outputs (no GroupNorm) are compared
-after dividing both sides by max(1, max|ref|), states likewise."""
+after dividing both sides by max(1, max|ref|), states likewise (fp32 bound for
+the recurrent kernel's states, a tenth of the bf16 bound for the chunkwise
+path's, whose products run on fp16 operands)."""
 import math
 
 import numpy as np
@@ -34,10 +36,15 @@ def host(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+# The chunkwise path forms its states from V * decay rounded to fp16 (11 significant bits, 2.4e-4 relative per
+# term) on the matrix cores with fp32 accumulation: its states are held to a tenth of the bf16 output bound.
+STATE_F16 = dict(max_abs=2e-3, mean_rel=1e-3)
+
+
 def check(got, ref, dtype, what, relative=False):
     unit = max(1.0, float(np.abs(ref).max())) if relative else 1.0
     st = ys.error_stats(got / unit, ref / unit)
-    tol = ys.TOL[dtype]
+    tol = STATE_F16 if dtype == "state_f16" else ys.TOL[dtype]
     print("%s: max_abs %.3e mean_rel %.3e (unit %.3g)" % (what, st["max_abs"], st["mean_rel"], unit), flush=True)
     assert np.isfinite(got).all(), what
     assert st["max_abs"] <= tol["max_abs"] and st["mean_rel"] <= tol["mean_rel"], (what, st)
@@ -115,3 +122,91 @@ def test_gret_empty_prefill_copies_the_state(yoco):
     yoco.gret_prefill(e, e, torch.empty(B, 0, H, dv, device="cuda"), torch.empty(B, 0, H, device="cuda"), 1.0,
                       state_in=None, state_out=s_out)
     assert torch.count_nonzero(s_out).item() == 0
+
+
+# ------------------------------------------------ chunkwise path on the matrix cores (Eq. 6)
+CHUNK_CASES = [
+    # B, T, H, chunk, group_norm, mean of -ln(gamma), carry a state in
+    (1, 700, 2, 256, True, 0.04, True),        # two whole chunks and a ragged one; several tiles with a ragged tail
+    (2, 1024, 3, 128, True, 0.04, False),      # chunk = one query block
+    (1, 1300, 2, 512, False, 0.04, True),      # raw output
+    (1, 1100, 1, 1024, True, 0.01, True),      # the largest chunk
+    (1, 100, 2, 256, True, 0.04, True),        # shorter than a chunk and than a query block
+    (1, 129, 2, 256, True, 0.04, False),       # one row into the second query block
+    (1, 640, 2, 256, True, 0.5, True),         # strong decay: gamma around 0.6, 2^-190 across a chunk
+    (1, 640, 2, 256, False, 0.0005, True),     # almost no decay: long memory, large states
+]
+
+
+@pytest.mark.parametrize("B,T,H,chunk,gn,mld,carry", CHUNK_CASES)
+def test_gret_prefill_chunkwise_matches_oracle(yoco, B, T, H, chunk, gn, mld, carry):
+    d = 128
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, lg = ys.gret_inputs(T + chunk, B, T, H, d, d, 1.0, "bf16", mean_log_decay=mld)
+    rng = np.random.default_rng(2)
+    S0 = rng.standard_normal((B, H, d, d)).astype(np.float32) if carry else None
+    s_in = torch.from_numpy(S0).cuda() if carry else None
+    s_out = torch.full((B, H, d, d), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = yoco.gret_prefill_workspace(B, T, H, d, d, chunk, yoco.BF16)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    args = (dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(lg).cuda(), scale)
+    o = yoco.gret_prefill(*args, chunk=chunk, group_norm=gn, eps=1e-6, state_in=s_in, state_out=s_out, workspace=ws)
+    torch.cuda.synchronize()
+    ref_o, ref_s = oracle_gret(q, k, v, lg, scale, gn, 1e-6, S0)
+    what = "gret chunkwise %s" % ((B, T, H, chunk, gn, mld, carry),)
+    check(host(o), ref_o, "bf16", what + " o", relative=not gn)
+    check(host(s_out), ref_s, "state_f16", what + " state", relative=True)
+    # the recurrent kernel on the same inputs (no workspace): both paths are the same function
+    s_rec = torch.empty_like(s_out)
+    o_rec = yoco.gret_prefill(*args, chunk=chunk, group_norm=gn, eps=1e-6, state_in=s_in, state_out=s_rec)
+    check(host(o), host(o_rec), "bf16", what + " against the recurrent kernel", relative=not gn)
+
+
+def test_gret_chunkwise_split_prompt_carries_the_state(yoco):
+    """A prompt processed as 384 + 516 rows with the state handed over equals one call over 900 rows."""
+    B, T, H, d, chunk = 1, 900, 2, 128, 256
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, lg = ys.gret_inputs(11, B, T, H, d, d, 1.0, "bf16")
+    ws = torch.empty(yoco.gret_prefill_workspace(B, T, H, d, d, chunk, yoco.BF16), dtype=torch.uint8, device="cuda")
+    qd, kd, vd, gd = dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(lg).cuda()
+    state = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    o1 = yoco.gret_prefill(qd[:, :384].contiguous(), kd[:, :384].contiguous(), vd[:, :384].contiguous(),
+                           gd[:, :384].contiguous(), scale, chunk=chunk, state_in=None, state_out=state, workspace=ws)
+    o2 = yoco.gret_prefill(qd[:, 384:].contiguous(), kd[:, 384:].contiguous(), vd[:, 384:].contiguous(),
+                           gd[:, 384:].contiguous(), scale, chunk=chunk, state_in=state, state_out=state, workspace=ws)
+    torch.cuda.synchronize()
+    ref_o, ref_s = oracle_gret(q, k, v, lg, scale, True, 1e-6)
+    check(np.concatenate([host(o1), host(o2)], axis=1), ref_o, "bf16", "gret chunkwise, split prompt")
+    check(host(state), ref_s, "state_f16", "gret chunkwise, split prompt: state", relative=True)
+
+
+def test_gret_prefill_without_enough_workspace_uses_the_recurrence(yoco):
+    B, T, H, d = 1, 300, 2, 128
+    q, k, v, lg = ys.gret_inputs(12, B, T, H, d, d, 1.0, "bf16")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    o = yoco.gret_prefill(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(lg).cuda(), 0.1, chunk=256,
+                          workspace=small)
+    torch.cuda.synchronize()
+    ref_o, _ = oracle_gret(q, k, v, lg, 0.1, True, 1e-6)
+    check(host(o), ref_o, "bf16", "gret with a workspace that is too small")
+    assert yoco.gret_prefill_workspace(B, T, H, 64, d, 256, yoco.BF16) == 0         # no chunkwise path for dk = 64
+    assert yoco.gret_prefill_workspace(B, T, H, d, d, 192, yoco.BF16) == 0          # nor for a chunk that is not n * 128
+
+
+def test_gret_prefill_full_size_sampled(yoco):
+    """The benchmark's gated-retention launch (T = 32768, 24 heads x 128, chunk 256, GroupNorm), three heads
+    checked row by row against the oracle's recurrence, and the final state of those heads."""
+    B, T, H, d, chunk = 1, 32768, 24, 128, 256
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, lg = ys.gret_inputs(0, B, T, H, d, d, 1.0, "bf16")
+    ws = torch.empty(yoco.gret_prefill_workspace(B, T, H, d, d, chunk, yoco.BF16), dtype=torch.uint8, device="cuda")
+    s_out = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    o = yoco.gret_prefill(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(lg).cuda(), scale, chunk=chunk,
+                          state_out=s_out, workspace=ws)
+    torch.cuda.synchronize()
+    got, gs = host(o), host(s_out)
+    for h in (0, 11, 23):
+        ref_o, ref_s = oracle_gret(q[:, :, h:h + 1], k[:, :, h:h + 1], v[:, :, h:h + 1], lg[:, :, h:h + 1], scale, True, 1e-6)
+        check(got[:, :, h:h + 1], ref_o, "bf16", "gret full size, head %d" % h)
+        check(gs[:, h:h + 1], ref_s, "state_f16", "gret full size, state of head %d" % h, relative=True)
