@@ -41,8 +41,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-decode", action="store_true", help="skip the two decode workloads")
-    ap.add_argument("--only", choices=["all", "swa", "decode", "calib"], default="all",
+    ap.add_argument("--only", choices=["all", "swa", "decode", "gret", "calib"], default="all",
                     help="profiling aid: 'swa' runs only the SWA prefill launches, 'decode' only the decode workloads, "
+                         "'gret' only the gated-retention launches, "
                          "'calib' only a 1 GiB device-to-device copy (the known-size kernel the HBM byte counters are scaled by)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -93,7 +94,7 @@ def main():
         args.no_decode = True
 
     def step(ev=None):
-        if args.only == "decode":
+        if args.only in ("decode", "gret"):
             return
         if ev:
             ev[0].record()
@@ -116,13 +117,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps if args.only != "decode" else float("nan")
+    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps if args.only not in ("decode", "gret") else float("nan")
     flops = swa_flops(T, H, d, C)
     swa_tflops = flops / (swa_ms * 1e-3) / 1e12
 
     # ---- the decode workloads of the metric: 13 cross-decoder layers over one shared cache
     decode = {}
-    if not args.no_decode:
+    if not args.no_decode and args.only != "gret":
         del q, k, v, o
         for name in ("decode_b16_32k", "decode_b1_512k"):
             dc = ys.CONFIGS[name]
@@ -190,6 +191,55 @@ def main():
         del rings, qs, w
         torch.cuda.empty_cache()
 
+    # ---- gated retention, the paper's other self-decoder module, at the same shape (reported, not part of `value`)
+    gret = None
+    if not args.no_decode and args.only in ("all", "gret"):
+        gq, gk, gv, glg = ys.gret_inputs(c["seed"], 1, T, H, d, d, 1.0, "bf16")
+        gq, gk, gv = (torch.from_numpy(x).to(dev).to(torch.bfloat16) for x in (gq, gk, gv))
+        glg = torch.from_numpy(glg).to(dev)
+        go = torch.empty_like(gv)
+        chunk = 256
+        gws = torch.empty(yoco.gret_prefill_workspace(1, T, H, d, d, chunk, yoco.BF16), dtype=torch.uint8, device=dev)
+        gst = torch.empty(1, H, d, d, dtype=torch.float32, device=dev)
+        times = []
+        for rep in range(3 + max(3, min(20, args.steps // 2))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            yoco.gret_prefill(gq, gk, gv, glg, scale, chunk=chunk, state_out=gst, workspace=gws, out=go)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 3:
+                times.append(e0.elapsed_time(e1))
+        ms = sum(times) / len(times)
+        gflops = T * H * (4.0 * d * (chunk + 1) / 2 + 4.0 * d * d)       # inner chunk (causal half) + cross-chunk + state
+        gret = {"prefill_32k": dict(ms=round(ms, 4), tokens_per_s=round(T / (ms * 1e-3), 1), chunk=chunk,
+                                    TFLOPs=round(gflops / (ms * 1e-3) / 1e12, 1),
+                                    workspace_bytes=gws.numel())}
+        del gq, gk, gv, go, gws
+        Bd, layers = 16, 13
+        states = [torch.zeros(Bd, H, d, d, dtype=torch.float32, device=dev) for _ in range(layers)]
+        dq = ys.device_normal((Bd, H, d), 600, 1.0, torch.bfloat16, dev)
+        dlg = -torch.rand(Bd, H, device=dev) * 0.1
+        do = torch.empty_like(dq)
+        times = []
+        for rep in range(2 + max(3, min(20, args.steps // 2))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(layers):
+                yoco.gret_decode(dq, dq, dq, dlg, states[i], scale, out=do)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                times.append(e0.elapsed_time(e1))
+        ms = sum(times) / len(times)
+        sbytes = 2.0 * Bd * H * d * d * 4                                  # the state read and written once
+        gret["decode_b16"] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4),
+                                  GBps=round(layers * sbytes / (ms * 1e-3) / 1e9, 1),
+                                  frac_of_hbm_peak=round(layers * sbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  state_bytes_per_layer=int(sbytes / 2))
+        del states
+        torch.cuda.empty_cache()
+
     # ---- the oracle on the host cores, bounded sample of the same SWA workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -223,6 +273,7 @@ def main():
                      "traffic": int(SWA_TRAFFIC_BYTES["fetch"] + SWA_TRAFFIC_BYTES["write"]),
                      "traffic_note": "HBM bytes per launch (fetch 0.631 GB + write 0.203 GB) against 0.805 GB algorithmic"},
         "decode": decode,
+        "gated_retention": gret,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

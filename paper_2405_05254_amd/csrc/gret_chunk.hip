@@ -97,7 +97,8 @@ __device__ __forceinline__ f16x8 tr_frag(lds_char* tile, int base, int blk, int 
 __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
   __shared__ __attribute__((aligned(1024))) char k_t[kTileBytes], v_t[kTileBytes];
   const GretView& a = g.a;
-  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // heads vary fastest over the grid: workgroups that run together read neighbouring 256-byte segments of the same rows
+  const int h = blockIdx.x, c = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hf = lane >> 5, lq = lane & 31;
@@ -123,24 +124,33 @@ __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int n_tiles = (int)((last - c0) / kBN) + 1;
+  u32x4 kr[4], vr[4];
+  float w[4];
+  auto load_tile = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t row = c0 + (int64_t)t0 * kBN + srow + 16 * i;
+      const int64_t grow = row <= last ? row : last;                // rows past the end weigh nothing
+      w[i] = row <= last ? __builtin_amdgcn_exp2f(g_last - gc[grow - c0]) : 0.f;
+      kr[i] = *(const u32x4*)(kg + grow * row_stride + c16 * 8);
+      vr[i] = *(const u32x4*)(vg + grow * row_stride + c16 * 8);
+    }
+  };
+  load_tile(0);
   for (int t0 = 0; t0 < n_tiles; ++t0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int lrow = srow + 16 * i;
-      const int64_t row = c0 + (int64_t)t0 * kBN + lrow;
-      const int64_t grow = row <= last ? row : last;                // rows past the end weigh nothing
-      const float w = row <= last ? __builtin_amdgcn_exp2f(g_last - gc[grow - c0]) : 0.f;
-      const u32x4 kr = *(const u32x4*)(kg + grow * row_stride + c16 * 8);
-      const u32x4 vr = *(const u32x4*)(vg + grow * row_stride + c16 * 8);
       u32x4 kh, vh;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        kh[e] = bf16x2_to_f16x2(kr[e]);
-        vh[e] = pack_f16(__uint_as_float(vr[e] << 16) * w, __uint_as_float(vr[e] & 0xffff0000u) * w);
+        kh[e] = bf16x2_to_f16x2(kr[i][e]);
+        vh[e] = pack_f16(__uint_as_float(vr[i][e] << 16) * w[i], __uint_as_float(vr[i][e] & 0xffff0000u) * w[i]);
       }
       *(u32x4*)(k_t + tr_store_off(lrow, c16)) = kh;
       *(u32x4*)(v_t + tr_store_off(lrow, c16)) = vh;
     }
+    if (t0 + 1 < n_tiles) load_tile(t0 + 1);                        // in flight during the products
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -165,8 +175,10 @@ __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
       }
 }
 
-// ---- launch 2: scan over the chunks; thread owns 4 consecutive elements of the state.
+// ---- launch 2: scan over the chunks; thread owns 4 consecutive elements of the state. The U_i of a
+// group of chunks are loaded together (independent addresses) before the dependent updates run.
 __global__ void __launch_bounds__(256) gret_state_scan_kernel(ChunkArgs g) {
+  constexpr int kAhead = 8;
   const GretView& a = g.a;
   const int h = blockIdx.y, b = blockIdx.z;
   const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -175,20 +187,31 @@ __global__ void __launch_bounds__(256) gret_state_scan_kernel(ChunkArgs g) {
   f32x4 R = {0.f, 0.f, 0.f, 0.f};
   if (a.state_in) R = *(const f32x4*)(a.state_in + bh * kState + e);
   const float* gc = g.gc + bh * g.nc * g.chunk;
-  for (int c = 0; c < g.nc; ++c) {
-    const int64_t off = (bh * g.nc + c) * kState + e;
-    u32x2 hi, lo;
+  for (int c0 = 0; c0 < g.nc; c0 += kAhead) {
+    f32x4 U[kAhead];
+    float alpha[kAhead];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      hi[p] = pack_bf16(R[2 * p], R[2 * p + 1]);
-      lo[p] = pack_bf16(R[2 * p] - __uint_as_float(hi[p] << 16), R[2 * p + 1] - __uint_as_float(hi[p] & 0xffff0000u));
+    for (int i = 0; i < kAhead; ++i) {
+      const int c = c0 + i < g.nc ? c0 + i : g.nc - 1;
+      U[i] = __builtin_nontemporal_load((const f32x4*)(g.u + (bh * g.nc + c) * kState + e));
+      alpha[i] = __builtin_amdgcn_exp2f(gc[last_row_of_chunk(g, c)]);
     }
-    *(u32x2*)(g.rhi + off) = hi;
-    *(u32x2*)(g.rlo + off) = lo;
-    if (c == g.nc - 1 && !a.state_out) break;
-    const float alpha = __builtin_amdgcn_exp2f(gc[last_row_of_chunk(g, c)]);
-    const f32x4 U = *(const f32x4*)(g.u + off);
-    R = U + alpha * R;
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) {
+      const int c = c0 + i;
+      if (c < g.nc) {
+        const int64_t off = (bh * g.nc + c) * kState + e;
+        u32x2 hi, lo;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          hi[p] = pack_bf16(R[2 * p], R[2 * p + 1]);
+          lo[p] = pack_bf16(R[2 * p] - __uint_as_float(hi[p] << 16), R[2 * p + 1] - __uint_as_float(hi[p] & 0xffff0000u));
+        }
+        *(u32x2*)(g.rhi + off) = hi;
+        *(u32x2*)(g.rlo + off) = lo;
+        R = U[i] + alpha[i] * R;
+      }
+    }
   }
   if (a.state_out) *(f32x4*)(a.state_out + bh * kState + e) = R;
 }
@@ -202,10 +225,10 @@ __global__ void __launch_bounds__(256, 2) gret_chunk_output_kernel(ChunkArgs g) 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hf = lane >> 5, lq = lane & 31;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, b = blockIdx.z;              // heads vary fastest over the grid, as in launch 1
   const int64_t bh = (int64_t)b * a.H + h;
 
-  const int64_t i0 = (int64_t)blockIdx.x * kBM;           // first query row of the workgroup
+  const int64_t i0 = (int64_t)blockIdx.y * kBM;           // first query row of the workgroup
   const int c = (int)(i0 / g.chunk);
   const int64_t c0 = (int64_t)c * g.chunk;
   const int64_t rows_here = a.T - i0 < kBM ? a.T - i0 : kBM;
@@ -416,9 +439,8 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 bool gret_chunk_supported(int B, int64_t T, int H, int dk, int dv, int chunk, int dtype) {
   if (dtype != YOCO_BF16 || dk != kD || dv != kD) return false;
   if (chunk % kBM || chunk > kMaxChunk) return false;
-  if (T <= 0 || T >= (1LL << 31) - kMaxChunk) return false;
-  const int64_t nc = (T + chunk - 1) / chunk;
-  return B <= 65535 && H <= 65535 && nc <= 0x7fffffff / 4;
+  if (T <= 0 || (T + kBM - 1) / kBM > 65535) return false;          // query blocks are the grid's y dimension
+  return B <= 65535;
 }
 
 size_t gret_chunk_workspace(int B, int64_t T, int H, int chunk) {
@@ -442,9 +464,9 @@ hipError_t launch_gret_chunk(const GretView& a, int chunk, void* workspace, hipS
   p += align256(bh * g.nc * kState * sizeof(bf16_t));
   g.rlo = (bf16_t*)p;
   hipLaunchKernelGGL(gret_cumdecay_kernel, dim3(g.nc, a.H, a.B), dim3(64), 0, s, g);
-  hipLaunchKernelGGL(gret_chunk_state_kernel, dim3(g.nc, a.H, a.B), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(gret_chunk_state_kernel, dim3(a.H, g.nc, a.B), dim3(256), 0, s, g);
   hipLaunchKernelGGL(gret_state_scan_kernel, dim3(kState / 1024, a.H, a.B), dim3(256), 0, s, g);
-  hipLaunchKernelGGL(gret_chunk_output_kernel, dim3((unsigned)((a.T + kBM - 1) / kBM), a.H, a.B), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(gret_chunk_output_kernel, dim3(a.H, (unsigned)((a.T + kBM - 1) / kBM), a.B), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 
