@@ -128,7 +128,9 @@ def yoco_stack(tokens, w, mode="full"):
     """Decoder-decoder stack (section 2, Eq. 1-3, Fig. 2) -> logits.
 
     w: dict with 'embed' [vocab,dm]; 'self' = list of layers with keys
-    ln1, W_Q, W_K, W_V, W_O, ln2, W_G, W_1, W_2; 'kv' = {ln, W_K, W_V};
+    ln1, W_Q, W_K, W_V, W_O, ln2, W_G, W_1, W_2 (and, when w['self_kind'] ==
+    'gret', W_gamma [dm,Hq] and W_gate [dm,Hq*d] with the temperature w['tau']:
+    the self-decoder then uses gated retention, Eq. 7); 'kv' = {ln, W_K, W_V};
     'cross' = list of layers with keys ln1, W_Q, W_O, ln2, W_G, W_1, W_2;
     'final_ln', 'W_out'; ints 'Hq', 'Hkv_self', 'Hkv', 'd', 'window'; 'eps'.
     mode 'full': every row goes through the cross-decoder -> logits [T,vocab].
@@ -141,11 +143,14 @@ def yoco_stack(tokens, w, mode="full"):
     T = X.shape[0]
     for L in w["self"]:                                   # Eq. 1
         Xn = rmsnorm(X, L["ln1"], eps)
-        Q = (Xn @ np.asarray(L["W_Q"], F64)).reshape(T, Hq, d)
-        K = (Xn @ np.asarray(L["W_K"], F64)).reshape(T, w["Hkv_self"], d)
-        V = (Xn @ np.asarray(L["W_V"], F64)).reshape(T, w["Hkv_self"], d)
-        A = swa(Q, K, V, w["window"], scale).reshape(T, Hq * d)
-        Y = A @ np.asarray(L["W_O"], F64) + X
+        if w.get("self_kind", "swa") == "gret":           # section 3.1: multi-head gated retention (Eq. 7)
+            Y = mhgr(Xn, L["W_Q"], L["W_K"], L["W_V"], L["W_gamma"], L["W_gate"], L["W_O"], Hq, w["tau"], scale, eps) + X
+        else:                                             # section 3.2: sliding-window attention (Eq. 8)
+            Q = (Xn @ np.asarray(L["W_Q"], F64)).reshape(T, Hq, d)
+            K = (Xn @ np.asarray(L["W_K"], F64)).reshape(T, w["Hkv_self"], d)
+            V = (Xn @ np.asarray(L["W_V"], F64)).reshape(T, w["Hkv_self"], d)
+            A = swa(Q, K, V, w["window"], scale).reshape(T, Hq * d)
+            Y = A @ np.asarray(L["W_O"], F64) + X
         X = swiglu(rmsnorm(Y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + Y
     Khat, Vhat = global_kv(X, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)  # Eq. 2
     if mode == "early_exit":
@@ -204,17 +209,26 @@ def yoco_stack_generate(tokens, w):
     identically whether the prompt is processed at once or token by token."""
     Hq, d, eps = w["Hq"], w["d"], w["eps"]
     scale = 1.0 / np.sqrt(d)
+    gret = w.get("self_kind", "swa") == "gret"
     rings = [RollingWindowCache(w["window"], w["Hkv_self"], d) for _ in w["self"]]
+    states = [None for _ in w["self"]]                    # gated retention keeps S_n (Eq. 5) instead of a ring
     Khat, Vhat = [], []
     out = []
     for p, tok in enumerate(np.asarray(tokens)):
         x = np.asarray(w["embed"], dtype=F64)[tok][None]              # [1,dm]
-        for L, ring in zip(w["self"], rings):
+        for li, (L, ring) in enumerate(zip(w["self"], rings)):
             xn = rmsnorm(x, L["ln1"], eps)
             q = (xn @ np.asarray(L["W_Q"], F64)).reshape(Hq, d)
-            ring.write(p, (xn @ np.asarray(L["W_K"], F64)).reshape(w["Hkv_self"], d),
-                       (xn @ np.asarray(L["W_V"], F64)).reshape(w["Hkv_self"], d))
-            a = ring.attend(q, p, scale).reshape(1, Hq * d)
+            kr = (xn @ np.asarray(L["W_K"], F64)).reshape(w["Hkv_self"], d)
+            vr = (xn @ np.asarray(L["W_V"], F64)).reshape(w["Hkv_self"], d)
+            if gret:
+                o, states[li] = gret_recurrent(q[None], kr[None], vr[None], gret_decay(xn, L["W_gamma"], w["tau"]), scale,
+                                               S0=states[li])
+                g = xn @ np.asarray(L["W_gate"], F64)
+                a = (g / (1.0 + np.exp(-g))) * group_norm_heads(o, eps).reshape(1, Hq * d)
+            else:
+                ring.write(p, kr, vr)
+                a = ring.attend(q, p, scale).reshape(1, Hq * d)
             y = a @ np.asarray(L["W_O"], F64) + x
             x = swiglu(rmsnorm(y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + y
         kh, vh = global_kv(x, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)

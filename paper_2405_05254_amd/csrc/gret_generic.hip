@@ -81,12 +81,15 @@ __global__ void __launch_bounds__(256) gret_recurrent_kernel(GretView a) {
     }
     float out[kRowsPerThread];
     float sum = 0.f;
+    const bool store_state = a.state_out && k_on && n == a.T - 1;
 #pragma unroll
     for (int r = 0; r < kRowsPerThread; ++r) {
       out[r] = 0.f;
       if (r < n_rows) {
         const float vv = Elem<T>::load(v + n * a.H * a.dv + rr + 8 * r);
         S[r] = gamma * S[r] + kf * vv;
+        // the final state leaves row by row, while later rows of a decode step are still arriving
+        if (store_state) *(f32x4*)(a.state_out + st_off + (size_t)(rr + 8 * r) * a.dk + ek) = S[r];
         const float part = qf[0] * S[r][0] + qf[1] * S[r][1] + qf[2] * S[r][2] + qf[3] * S[r][3];
         out[r] = a.scale * half_wave_sum(part);
         sum += out[r];
@@ -111,11 +114,6 @@ __global__ void __launch_bounds__(256) gret_recurrent_kernel(GretView a) {
     }
   }
 
-  if (a.state_out && k_on) {
-#pragma unroll
-    for (int r = 0; r < kRowsPerThread; ++r)
-      if (r < n_rows) *(f32x4*)(a.state_out + st_off + (size_t)(rr + 8 * r) * a.dk + ek) = S[r];
-  }
 }
 
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* p, size_t n) {

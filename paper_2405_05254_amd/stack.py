@@ -49,6 +49,7 @@ class YocoStack:
         w = weights
         self.Hq, self.Hkv_self, self.Hkv, self.d = w["Hq"], w["Hkv_self"], w["Hkv"], w["d"]
         self.window, self.eps = w["window"], w["eps"]
+        self.self_kind, self.tau = w.get("self_kind", "swa"), w.get("tau", 16.0)   # "swa" (Eq. 8) or "gret" (Eq. 7)
         self.scale = 1.0 / math.sqrt(self.d)
         self.embed = dev(w["embed"])
         self.self_layers = [layer(L) for L in w["self"]]
@@ -57,8 +58,13 @@ class YocoStack:
         self.final_ln, self.W_out = dev(w["final_ln"]), dev(w["W_out"])
 
     # -- self-decoder: Eq. 1 with sliding-window attention (Eq. 8)
+    def _log_decay(self, xn, L):
+        """ln(gamma) of Eq. 4: logsigmoid(x W_gamma) / tau, float32 [rows, H]."""
+        return (torch.nn.functional.logsigmoid(xn.float() @ L["W_gamma"].float()) / self.tau).contiguous()
+
     def self_decoder(self, tokens, rings=None):
-        """rings: optional list of rolling caches (one per layer) that receive the last `window` K/V rows."""
+        """rings: optional per-layer generation caches that receive what a later decode step needs: rolling
+        caches (the last `window` K/V rows) for sliding-window attention, fp32 states for gated retention."""
         X = self.embed[tokens]
         T = X.shape[0]
         for n, L in enumerate(self.self_layers):
@@ -66,13 +72,24 @@ class YocoStack:
             q = (xn @ L["W_Q"]).to(self.dtype).view(1, T, self.Hq, self.d)
             k = (xn @ L["W_K"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
             v = (xn @ L["W_V"]).to(self.dtype).view(1, T, self.Hkv_self, self.d)
-            o = yb.swa_prefill(q, k, v, self.window, self.scale)
-            if rings is not None:
-                yb.swa_cache_write(rings[n], k[0], v[0], 0, 0)
+            if self.self_kind == "gret":
+                lg = self._log_decay(xn, L).view(1, T, self.Hq)
+                code = yb.F32 if self.dtype == torch.float32 else yb.BF16
+                nbytes = yb.gret_prefill_workspace(1, T, self.Hq, self.d, self.d, 256, code)
+                ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device) if nbytes else None
+                o = yb.gret_prefill(q, k, v, lg, self.scale, chunk=256, group_norm=True, eps=self.eps,
+                                    state_out=None if rings is None else rings[n], workspace=ws)
+                a = torch.nn.functional.silu(xn @ L["W_gate"]) * o.view(T, self.Hq * self.d).to(self.glue)
+                del ws, lg
+            else:
+                o = yb.swa_prefill(q, k, v, self.window, self.scale)
+                if rings is not None:
+                    yb.swa_cache_write(rings[n], k[0], v[0], 0, 0)
+                a = o.view(T, self.Hq * self.d).to(self.glue)
             if self.capture is not None and ("self%d" % n) in self.capture:
                 self.capture["self%d" % n] = (q[0], k[0], v[0], o[0])
-            Y = o.view(T, self.Hq * self.d).to(self.glue) @ L["W_O"] + X
-            del q, k, v, o, xn
+            Y = a @ L["W_O"] + X
+            del q, k, v, o, xn, a
             X = _rows(Y, lambda y: _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y)
         return X
 
@@ -145,12 +162,16 @@ class YocoStack:
 
     # -- token-by-token generation (Fig. 3 "Generation"): rolling caches in the self-decoder
     def new_generation_state(self, max_len):
-        """Caches of one sequence: a ring of `window` rows per self-decoder layer and the global cache."""
-        rings = [yb.KVCache(1, self.Hkv_self, self.d, self.window, self.dtype, self.device) for _ in self.self_layers]
+        """Caches of one sequence: per self-decoder layer a ring of `window` rows (sliding-window attention) or an
+        fp32 state (gated retention), and the global cache."""
+        if self.self_kind == "gret":
+            rings = [torch.zeros(1, self.Hq, self.d, self.d, dtype=torch.float32, device=self.device) for _ in self.self_layers]
+        else:
+            rings = [yb.KVCache(1, self.Hkv_self, self.d, self.window, self.dtype, self.device) for _ in self.self_layers]
         cache = yb.KVCache(1, self.Hkv, self.d, max_len, self.dtype, self.device)
         ws = []
-        for c, Hq in ((rings[0], self.Hq), (cache, self.Hq)):
-            nbytes, _ = yb.cross_attn_decode_workspace(c, Hq)
+        for c in ((cache, cache) if self.self_kind == "gret" else (rings[0], cache)):
+            nbytes, _ = yb.cross_attn_decode_workspace(c, self.Hq)
             ws.append(torch.empty(nbytes, dtype=torch.uint8, device=self.device))
         return dict(rings=rings, cache=cache, ws_ring=ws[0], ws_cache=ws[1], length=0)
 
@@ -178,9 +199,15 @@ class YocoStack:
             q = (xn @ L["W_Q"]).to(self.dtype).view(1, self.Hq, self.d)
             k = (xn @ L["W_K"]).to(self.dtype).view(1, self.Hkv_self, self.d)
             v = (xn @ L["W_V"]).to(self.dtype).view(1, self.Hkv_self, self.d)
-            yb.kv_cache_append(ring, k, v, pos, True)
-            o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"])
-            y = o.view(1, self.Hq * self.d).to(self.glue) @ L["W_O"] + x
+            if self.self_kind == "gret":
+                o = yb.gret_decode(q, k, v, self._log_decay(xn, L).view(1, self.Hq), ring, self.scale, group_norm=True,
+                                   eps=self.eps)
+                a = torch.nn.functional.silu(xn @ L["W_gate"]) * o.view(1, self.Hq * self.d).to(self.glue)
+            else:
+                yb.kv_cache_append(ring, k, v, pos, True)
+                o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"])
+                a = o.view(1, self.Hq * self.d).to(self.glue)
+            y = a @ L["W_O"] + x
             x = _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y
         xn = _rmsnorm(x, self.kv["ln"], self.eps)
         k = (xn @ self.kv["W_K"]).to(self.dtype).view(1, self.Hkv, self.d)

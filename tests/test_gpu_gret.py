@@ -210,3 +210,61 @@ def test_gret_prefill_full_size_sampled(yoco):
         ref_o, ref_s = oracle_gret(q[:, :, h:h + 1], k[:, :, h:h + 1], v[:, :, h:h + 1], lg[:, :, h:h + 1], scale, True, 1e-6)
         check(got[:, :, h:h + 1], ref_o, "bf16", "gret full size, head %d" % h)
         check(gs[:, h:h + 1], ref_s, "state_f16", "gret full size, state of head %d" % h, relative=True)
+
+
+# ------------------------------------------------ the stack with a gated-retention self-decoder
+def test_tiny_gret_stack_matches_oracle(yoco):
+    """Tiny fp32 stack whose self-decoder is multi-head gated retention (Eq. 7): full forward against the
+    oracle, early exit against the full forward, and prompt + teacher-forced decode steps (recurrent state
+    carried from the prefill) against the oracle's all-at-once logits."""
+    from paper_2405_05254_amd.stack import YocoStack
+    c = ys.CONFIGS["tiny_fp32"]
+    spec = dict(c["stack"], self_kind="gret", tau=16.0)
+    w = ys.stack_weights(c["seed"], spec, "f32")
+    T0, steps = 300, 30
+    tok = ys.tokens(c["seed"] + 3, T0 + steps, spec["vocab"])
+    ref = oracle.yoco_stack(tok, w, "full")
+    st = YocoStack(w, torch.float32)
+    t = torch.from_numpy(tok).cuda()
+    full = host(st.forward_full(t))
+    ee = host(st.forward_early_exit(t)[0])
+    print("gret stack: full vs oracle %.3e, early exit vs full %.3e" % (np.abs(full - ref).max(), np.abs(ee[0] - full[-1]).max()),
+          flush=True)
+    assert np.abs(full - ref).max() <= 1e-3
+    assert np.abs(ee[0] - full[-1]).max() <= 1e-3
+    state = st.new_generation_state(T0 + steps)
+    logits = [host(st.prefill(t[:T0], state))[0]]
+    for i in range(steps):
+        logits.append(host(st.decode_step(t[T0 + i], state))[0])
+    err = np.abs(np.stack(logits) - ref[T0 - 1:]).max()
+    print("gret stack: prefill + %d decode steps vs oracle %.3e" % (steps, err), flush=True)
+    assert err <= 1e-3
+
+
+def test_bf16_gret_stack_early_exit_and_generation(yoco):
+    """The end-to-end architecture with a gated-retention self-decoder (d_model 2048, 16 x 128 heads, reduced to
+    3 + 3 layers) at T = 3000, bf16: the chunkwise MFMA path in the prefill. Early exit against the GPU full
+    forward (Fig. 3: same kernels on both sides, 1e-3), and a prompt + decode run against the full forward's rows.
+    The decode steps run the recurrent kernel where the full forward ran the chunkwise one: the two agree to one
+    bf16 rounding of each attention output (2^-9 relative, checked kernel against kernel above), and six layers of
+    independently rounded outputs move a logit by about 0.3 % of the logit scale rms; the bound is 2 % of the
+    largest logit. The fp32 stack above pins the same flow to 1e-3 absolute."""
+    from paper_2405_05254_amd.stack import YocoStack
+    c = ys.CONFIGS["e2e_early_exit_128k"]
+    s = dict(c["stack"], n_self=3, n_cross=3, vocab=4096, self_kind="gret", tau=16.0)
+    T = 3000
+    w = ys.stack_weights(c["seed"], s, "bf16")
+    tok = torch.from_numpy(ys.tokens(c["seed"], T, s["vocab"])).cuda()
+    st = YocoStack(w, torch.bfloat16)
+    full = host(st.forward_full(tok, rows=slice(T - 9, T)))
+    ee = host(st.forward_early_exit(tok)[0])
+    err = np.abs(ee - full[-1:]).max()
+    print("bf16 gret stack early-exit vs full: %.3e (logit scale %.3f)" % (err, np.abs(full).max()), flush=True)
+    assert err <= 1e-3
+    state = st.new_generation_state(T)
+    logits = [host(st.prefill(tok[:T - 8], state))[0]]
+    for i in range(T - 8, T):
+        logits.append(host(st.decode_step(tok[i], state))[0])
+    err = np.abs(np.stack(logits) - full).max()
+    print("bf16 gret stack prompt + 8 decode steps vs full forward: %.3e" % err, flush=True)
+    assert err <= 0.02 * np.abs(full).max()

@@ -463,3 +463,26 @@ def test_mhgr_matches_library_composition():
     y = F.group_norm(heads.transpose(0, 1).reshape(T, H * dh), H, eps=1e-6)
     ref = ((F.silu(x @ torch.from_numpy(Ws["W_G"])) * y) @ torch.from_numpy(Ws["W_O"])).numpy()
     assert np.abs(got - ref).max() < 1e-10
+
+
+GRET_SMALL = dict(SMALL, Hkv_self=4, self_kind="gret", tau=4.0)
+
+
+def test_gret_stack_early_exit_prefix_and_generation_invariants():
+    """The stack with a gated-retention self-decoder: early exit = last row of the full forward (Fig. 3), a
+    prefix's logits do not depend on later tokens, and token-by-token generation with the recurrent state
+    (Eq. 5) reproduces the all-at-once forward, which uses the parallel form (Eq. 4)."""
+    w = ys.stack_weights(3, GRET_SMALL, "f32")
+    for k in ("self", "cross"):
+        for L in w[k]:
+            for n in ("W_Q", "W_K", "W_V"):
+                if n in L:
+                    L[n] = L[n] * 30
+    tok = ys.tokens(3, 23, 50)
+    full = oracle.yoco_stack(tok, w, "full")
+    assert np.abs(oracle.yoco_stack(tok, w, "early_exit")[0] - full[-1]).max() < 1e-11
+    assert np.abs(oracle.yoco_stack(tok[:9], w, "early_exit")[0] - full[8]).max() < 1e-11
+    assert np.abs(oracle.yoco_stack_generate(tok, w) - full).max() < 1e-10
+    # and it is a different model from the sliding-window variant with the same shared matrices
+    w_swa = ys.stack_weights(3, dict(SMALL, Hkv_self=4), "f32")
+    assert np.abs(oracle.yoco_stack(tok, w_swa, "full") - oracle.yoco_stack(tok, ys.stack_weights(3, GRET_SMALL, "f32"), "full")).max() > 1e-4

@@ -104,6 +104,11 @@ def stack_weights(seed, s, dtype):
                   for _ in range(s["n_cross"])]
     w["final_ln"] = ones()
     w["W_out"] = mat(dm, s["vocab"])
+    if s.get("self_kind", "swa") == "gret":           # gated-retention self-decoder: decay and gate projections
+        w["self_kind"], w["tau"] = "gret", s.get("tau", 16.0)
+        for L in w["self"]:                           # drawn last, so the other matrices match the SWA variant's
+            L["W_gamma"] = normal(rng, (dm, Hq), 1.0, dtype)
+            L["W_gate"] = mat(dm, Hq * d)
     return w
 
 
