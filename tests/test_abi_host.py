@@ -137,3 +137,47 @@ def test_generation_calls_validate_before_launching():
     assert L.yoco_swa_decode(C.byref(d), p, p, p, 3, 1.0, p, n.value, None) == -1       # Hq % Hkv
     assert L.yoco_swa_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
     assert L.yoco_swa_decode(C.byref(d), p, p, p, 4, 1.0, p + 1, n.value, None) == -3
+
+
+def test_gated_retention_calls_validate_before_launching():
+    L = yoco.lib()
+    p = 0x7f0000000000
+    n = C.c_size_t()
+    # workspace sizing: only bf16, dk = dv = 128, chunk a multiple of 128 has a chunkwise path
+    assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 256, yoco.BF16, C.byref(n)) == 0
+    nc = 4
+    assert n.value == 4 * (nc * 256 * 4 + nc * 128 * 128 * 4 + 2 * nc * 128 * 128 * 2)
+    for args in ((1, 1000, 4, 64, 128, 256, yoco.BF16), (1, 1000, 4, 128, 128, 256, yoco.F32), (1, 1000, 4, 128, 128, 200, yoco.BF16)):
+        assert L.yoco_gret_prefill_workspace(*args, C.byref(n)) == 0 and n.value == 0
+    assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 0, yoco.BF16, C.byref(n)) == -1
+    assert L.yoco_gret_prefill_workspace(1, 1000, 4, 100, 128, 256, yoco.BF16, C.byref(n)) == -3
+    assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 256, yoco.BF16, None) == -1
+
+    def prefill(q=p, k=p, v=p, g=p, o=p, s_in=None, s_out=None, B=1, T=10, H=2, dk=128, dv=128, chunk=256, eps=1e-6, dt=yoco.BF16,
+                ws=None, wsb=0):
+        return L.yoco_gret_prefill(q, k, v, g, o, s_in, s_out, B, T, H, dk, dv, chunk, 1.0, 1, eps, dt, ws, wsb, None)
+    assert prefill(q=None) == -1
+    assert prefill(g=None) == -1
+    assert prefill(v=p + 8) == -3
+    assert prefill(g=p + 2) == -3
+    assert prefill(s_in=p + 4) == -3
+    assert prefill(ws=p + 16, wsb=1 << 30) == -3
+    assert prefill(T=-1) == -1
+    assert prefill(H=0) == -1
+    assert prefill(chunk=0) == -1
+    assert prefill(eps=-1.0) == -1
+    assert prefill(dt=3) == -2
+    assert prefill(dk=12) == -3
+    assert prefill(dk=264) == -2
+    assert prefill(dk=256, dv=256, dt=yoco.F32) == -2                  # valid dims, but no kernel above 128
+    assert b"no kernel" in L.yoco_last_error_string()
+    assert prefill(T=0, q=None, k=None, v=None, g=None, o=None) == 0   # empty prompt, no state to copy
+
+    def decode(q=p, k=p, v=p, g=p, o=p, st=p, B=2, H=2, dk=128, dv=128, eps=1e-6, dt=yoco.BF16):
+        return L.yoco_gret_decode(q, k, v, g, o, st, B, H, dk, dv, 1.0, 1, eps, dt, None)
+    assert decode(st=None) == -1
+    assert decode(o=p + 2) == -3
+    assert decode(B=0) == -1
+    assert decode(dv=4) == -3
+    assert decode(dt=-1) == -2
+    assert decode(dk=136, dt=yoco.F32) == -2
