@@ -203,6 +203,10 @@ int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int
  * S is stored transposed so that its rows run along the key dimension.
  * state_in: the state before row 0 (NULL = zeros); state_out: receives the
  * state after the last row (NULL = not stored); they may be the same memory.
+ * Domain of the chunkwise bf16 path: its products run on fp16 operands, so
+ * |k|, |v| and |scale * q.k| must stay below 65504 (magnitudes under 2^-14
+ * lose low bits or flush, an absolute error below 2^-25); the recurrent
+ * kernel computes in fp32 and has no such limit.
  */
 
 /* Scratch bytes yoco_gret_prefill needs for its chunkwise path on this shape

@@ -21,6 +21,9 @@
 //
 // Orientation, tiling, LDS swizzles, the fp16 second product (P rounded to fp16,
 // V converted while staged) are those of swa_mfma.hip, for the same reasons.
+// Launch 1 converts K as well (both operands of its product are fp16), and the
+// weights scale * s * decay are not bounded by 1 as softmax weights are: |k|,
+// |v| and |scale * q.k| of 65520 or more are outside these kernels' domain.
 #include "mfma_util.h"
 #include "yoco_common.h"
 

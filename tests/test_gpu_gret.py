@@ -138,6 +138,23 @@ CHUNK_CASES = [
 ]
 
 
+def test_gret_chunkwise_large_magnitudes(yoco):
+    """Inputs of standard deviation 4 (scores of magnitude ~100 before the scale, states in the thousands):
+    far from the fp16 limits of the chunkwise path, results still within the bounds."""
+    B, T, H, d, chunk = 1, 700, 2, 128, 256
+    scale = 1.0 / math.sqrt(d)
+    q, k, v, lg = ys.gret_inputs(31, B, T, H, d, d, 4.0, "bf16")
+    ws = torch.empty(yoco.gret_prefill_workspace(B, T, H, d, d, chunk, yoco.BF16), dtype=torch.uint8, device="cuda")
+    s_out = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda")
+    for gn in (True, False):
+        o = yoco.gret_prefill(dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(lg).cuda(), scale, chunk=chunk,
+                              group_norm=gn, state_out=s_out, workspace=ws)
+        torch.cuda.synchronize()
+        ref_o, ref_s = oracle_gret(q, k, v, lg, scale, gn, 1e-6)
+        check(host(o), ref_o, "bf16", "gret chunkwise, std 4, group_norm=%s" % gn, relative=not gn)
+    check(host(s_out), ref_s, "state_f16", "gret chunkwise, std 4: state", relative=True)
+
+
 @pytest.mark.parametrize("B,T,H,chunk,gn,mld,carry", CHUNK_CASES)
 def test_gret_prefill_chunkwise_matches_oracle(yoco, B, T, H, chunk, gn, mld, carry):
     d = 128
