@@ -22,7 +22,7 @@ the closed forms gamma = 1 (causal prefix sums) and gamma -> 0 (only the
 diagonal term), and GroupNorm by torch's group_norm.
 No function here is "parity unpinned".
 
-Readings of points the paper leaves open (all listed in the design doc):
+Readings of points the paper leaves open:
   * `scale` is an explicit argument; Eq. 8 prints no 1/sqrt(d), Eq. 3 defers
     to "standard multi-head attention". The configurations use 1/sqrt(d).
   * Eq. 8's mask  i - C < j <= i  means a row sees itself and the C-1 keys
