@@ -39,6 +39,9 @@
  *     calling thread.
  *   - Arithmetic: products of the stored dtype, fp32 accumulation and fp32
  *     softmax; outputs are rounded once (to nearest even) to the dtype.
+ *   - Calls on different streams may run concurrently as long as they do not
+ *     share a workspace, a state, or cache rows one of them writes; the
+ *     library keeps no state of its own between calls.
  */
 #ifndef YOCO_H
 #define YOCO_H
