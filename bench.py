@@ -46,6 +46,7 @@ def main():
                          "'gret' only the gated-retention launches, "
                          "'calib' only a 1 GiB device-to-device copy (the known-size kernel the HBM byte counters are scaled by)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-e2e", action="store_true", help="skip the whole-stack prefill timing at T = 131072")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -240,6 +241,35 @@ def main():
         del states
         torch.cuda.empty_cache()
 
+    # ---- whole-stack context (not part of `value`): the end-to-end configuration's prefill at T = 131072, once
+    # with the early exit of Fig. 3 and once with every row sent through the cross-decoder. The projections,
+    # norms and FFNs are torch bf16 GEMMs (not part of the library); attention and the cache are libyoco's.
+    e2e = None
+    if args.only == "all" and not args.no_e2e:
+        from paper_2405_05254_amd.stack import YocoStack
+        ec = ys.CONFIGS["e2e_early_exit_128k"]
+        with torch.no_grad():
+            w = ys.stack_weights_device(ec["seed"], ec["stack"], torch.bfloat16, dev)
+            st = YocoStack(w, torch.bfloat16, glue_dtype=torch.bfloat16)
+            del w
+            tok = torch.from_numpy(ys.tokens(ec["seed"], ec["T"], ec["stack"]["vocab"])).to(dev)
+
+            def timed(fn):
+                fn()                                  # warm-up (GEMM heuristics, allocator)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3
+
+            ee_ms = timed(lambda: st.forward_early_exit(tok))
+            full_ms = timed(lambda: st.forward_full(tok, rows=slice(ec["T"] - 1, ec["T"])))
+            del st, tok
+            torch.cuda.empty_cache()
+        e2e = dict(T=ec["T"], early_exit_prefill_ms=round(ee_ms, 1), full_forward_ms=round(full_ms, 1),
+                   early_exit_speedup=round(full_ms / ee_ms, 2), early_exit_tokens_per_s=round(ec["T"] / (ee_ms * 1e-3), 1),
+                   note="1.4B-shape random-init stack, 12 + 12 layers, bf16 torch GEMMs around libyoco's attention")
+
     # ---- the oracle on the host cores, bounded sample of the same SWA workload
     cpu = None
     if not args.no_cpu_baseline:
@@ -274,6 +304,7 @@ def main():
                      "traffic_note": "HBM bytes per launch (fetch 0.631 GB + write 0.203 GB) against 0.805 GB algorithmic"},
         "decode": decode,
         "gated_retention": gret,
+        "e2e_early_exit_128k": e2e,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
