@@ -274,18 +274,14 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = 1
         rng = np.random.default_rng(1)
-        n, t0 = 0, time.perf_counter()
+        n, t0, c0 = 0, time.perf_counter(), time.process_time()
         while time.perf_counter() - t0 < args.cpu_seconds:
             for _ in range(64):
                 oracle.swa_row(qn, kn, vn, int(rng.integers(C, T)), int(rng.integers(0, H)), C, scale)
             n += 64
         dt = time.perf_counter() - t0
+        cores = max(1, int(round((time.process_time() - c0) / dt)))      # threads that were actually busy (CPU time / wall time)
         cpu = dict(value=round(n / H / dt, 3), unit="tokens/s", cores=cores, kind="oracle",
                    sample="%d sampled (row, head) outputs of the same T=32768 x 24-head SWA workload in %.1f s; "
                           "a token = 24 head rows" % (n, dt))
