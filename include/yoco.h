@@ -200,8 +200,9 @@ int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int
  * all of `dtype`. Eq. 4 prints no scale; any value cancels in the GroupNorm.
  * The rotation Theta of Eq. 4 is the caller's (q and k arrive rotated, or not).
  * group_norm != 0 applies Eq. 7's GroupNorm_h to every head's dv-vector before
- * it is stored: (o - mean) / sqrt(var + eps), no learned affine; the swish gate
- * and W_O of Eq. 7 are the caller's.
+ * it is stored: (o - mean) / sqrt(var + eps), no learned affine. gate (NULL =
+ * none; else like v, the caller's X W_G) multiplies the result by swish(gate) =
+ * gate * sigmoid(gate), the gate of Eq. 7; W_O is the caller's.
  * States are fp32 [B,H,dv,dk]: element (e_v, e_k) is S[e_k][e_v] of Eq. 5, i.e.
  * S is stored transposed so that its rows run along the key dimension.
  * state_in: the state before row 0 (NULL = zeros); state_out: receives the
@@ -224,16 +225,16 @@ int yoco_gret_prefill_workspace(int B, int64_t T, int H, int dk, int dv, int chu
  * other case runs the recurrence, which computes the same function (dk, dv <=
  * 128). T == 0 copies state_in to state_out.
  */
-int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, void* o,
+int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, const void* gate, void* o,
                       const float* state_in, float* state_out, int B, int64_t T, int H, int dk, int dv, int chunk,
                       float scale, int group_norm, float eps, int dtype, void* workspace, size_t workspace_bytes,
                       void* stream);
 
 /*
  * One generation step (Eq. 5) for one new row per sequence: q, k: [B,H,dk];
- * v, o: [B,H,dv]; log_gamma: [B,H]; state: [B,H,dv,dk] fp32, updated in place.
+ * v, gate, o: [B,H,dv]; log_gamma: [B,H]; state: [B,H,dv,dk] fp32, updated in place.
  */
-int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, void* o, float* state,
+int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, const void* gate, void* o, float* state,
                      int B, int H, int dk, int dv, float scale, int group_norm, float eps, int dtype, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). */

@@ -6,6 +6,6 @@ use it. It shares no code with the HIP path.
 """
 from .yoco_oracle import (  # noqa: F401
     swa_row, swa, rmsnorm, global_kv, cross_attn_row, cross_attn,
-    swiglu, yoco_stack, kv_cache_bytes_per_token, RollingWindowCache, yoco_stack_generate,
+    swish, swiglu, yoco_stack, kv_cache_bytes_per_token, RollingWindowCache, yoco_stack_generate,
     gret_decay, gret_parallel, gret_recurrent, gret_chunkwise, group_norm_heads, mhgr,
 )

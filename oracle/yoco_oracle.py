@@ -115,6 +115,12 @@ def cross_attn(Q, Khat, Vhat, q_pos0, scale):
     return O
 
 
+def swish(x):
+    """swish(x) = x * sigmoid(x) (sections 2.1 and 3.1)."""
+    x = np.asarray(x, dtype=F64)
+    return x / (1.0 + np.exp(-x))
+
+
 def swiglu(X, W_G, W_1, W_2):
     """SwiGLU(X) = (swish(X W_G) * X W_1) W_2 with swish(x) = x * sigmoid(x)
     (section 2.1)."""

@@ -47,8 +47,8 @@ def lib():
     L.yoco_kv_cache_append.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, i32, vp]
     L.yoco_swa_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
     L.yoco_gret_prefill_workspace.argtypes = [i32, i64, i32, i32, i32, i32, i32, C.POINTER(sz)]
-    L.yoco_gret_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, f32, i32, f32, i32, vp, sz, vp]
-    L.yoco_gret_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, f32, i32, vp]
+    L.yoco_gret_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, f32, i32, f32, i32, vp, sz, vp]
+    L.yoco_gret_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, f32, i32, vp]
     for name in ("yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
                  "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode",
                  "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode",
@@ -215,27 +215,31 @@ def _state(t, name, B, H, dk, dv):
 
 
 def gret_prefill(q, k, v, log_gamma, scale, chunk=256, group_norm=True, eps=1e-6, state_in=None, state_out=None,
-                 workspace=None, out=None):
+                 workspace=None, out=None, gate=None):
     """q, k [B,T,H,dk]; v [B,T,H,dv]; log_gamma float32 [B,T,H] -> o [B,T,H,dv] (yoco_gret_prefill).
-    States are float32 [B,H,dv,dk]; workspace: device tensor from gret_prefill_workspace bytes (None: recurrent path)."""
+    States are float32 [B,H,dv,dk]; workspace: device tensor from gret_prefill_workspace bytes (None: recurrent path);
+    gate: optional tensor like v, the output is multiplied by swish(gate)."""
     B, T, H, dk = q.shape
     dv = v.shape[3]
     if k.shape != q.shape or v.shape[:3] != q.shape[:3] or k.dtype != q.dtype or v.dtype != q.dtype:
         raise YocoError("q/k/v shapes or dtypes disagree")
     if log_gamma.dtype != torch.float32 or log_gamma.shape != (B, T, H):
         raise YocoError("log_gamma must be float32 [B,T,H]")
+    if gate is not None and (gate.shape != v.shape or gate.dtype != v.dtype):
+        raise YocoError("gate must match v")
     o = torch.empty_like(v) if out is None else out
     ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().yoco_gret_prefill(_dev(q, "q") if T else None, _dev(k, "k") if T else None, _dev(v, "v") if T else None,
-                                   _dev(log_gamma, "log_gamma") if T else None, _dev(o, "o") if T else None,
+                                   _dev(log_gamma, "log_gamma") if T else None,
+                                   _dev(gate, "gate") if (T and gate is not None) else None, _dev(o, "o") if T else None,
                                    _state(state_in, "state_in", B, H, dk, dv), _state(state_out, "state_out", B, H, dk, dv),
                                    B, T, H, dk, dv, chunk, scale, int(bool(group_norm)), eps, _dtype(q), ws_ptr, ws_bytes,
                                    _stream()))
     return o
 
 
-def gret_decode(q, k, v, log_gamma, state, scale, group_norm=True, eps=1e-6, out=None):
+def gret_decode(q, k, v, log_gamma, state, scale, group_norm=True, eps=1e-6, out=None, gate=None):
     """q, k [B,H,dk]; v [B,H,dv]; log_gamma float32 [B,H]; state float32 [B,H,dv,dk], updated in place
     -> o [B,H,dv] (yoco_gret_decode)."""
     B, H, dk = q.shape
@@ -244,8 +248,11 @@ def gret_decode(q, k, v, log_gamma, state, scale, group_norm=True, eps=1e-6, out
         raise YocoError("q/k/v shapes or dtypes disagree")
     if log_gamma.dtype != torch.float32 or log_gamma.shape != (B, H):
         raise YocoError("log_gamma must be float32 [B,H]")
+    if gate is not None and (gate.shape != v.shape or gate.dtype != v.dtype):
+        raise YocoError("gate must match v")
     o = torch.empty_like(v) if out is None else out
-    _check(lib().yoco_gret_decode(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(log_gamma, "log_gamma"), _dev(o, "o"),
+    _check(lib().yoco_gret_decode(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(log_gamma, "log_gamma"),
+                                  _dev(gate, "gate") if gate is not None else None, _dev(o, "o"),
                                   _state(state, "state", B, H, dk, dv), B, H, dk, dv, scale, int(bool(group_norm)), eps,
                                   _dtype(q), _stream()))
     return o

@@ -15,7 +15,8 @@
 //   3  outputs, one workgroup per 128 query rows: the cross-chunk product
 //      R_{i-1}^T Q^T (bf16 MFMA on hi and lo) scaled per row, then the key
 //      tiles of the chunk up to the diagonal as in the sliding-window kernel,
-//      with the decay 2^(G_j - G_k) in place of the softmax; optional GroupNorm.
+//      with the decay 2^(G_j - G_k) in place of the softmax; optional GroupNorm
+//      and swish gate (Eq. 7) before the store.
 // States and U are stored transposed ([dv][dk]); this is also the layout of
 // the caller's state_in / state_out.
 //
@@ -423,13 +424,24 @@ __global__ void __launch_bounds__(256, 2) gret_chunk_output_kernel(ChunkArgs g) 
     rstd = rsqrtf(sq * (1.f / kD) + a.eps);
   }
   if (q_valid) {
-    bf16_t* og = (bf16_t*)a.o + (((int64_t)b * a.T + iq) * a.H + h) * kD;
+    const int64_t row_off = (((int64_t)b * a.T + iq) * a.H + h) * kD;
+    bf16_t* og = (bf16_t*)a.o + row_off;
+    const bf16_t* gg = a.gate ? (const bf16_t*)a.gate + row_off : nullptr;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        const u32x2 w = {pack_bf16((acc_o[mb][rq * 4] - mean) * rstd, (acc_o[mb][rq * 4 + 1] - mean) * rstd),
-                         pack_bf16((acc_o[mb][rq * 4 + 2] - mean) * rstd, (acc_o[mb][rq * 4 + 3] - mean) * rstd)};
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = (acc_o[mb][rq * 4 + e] - mean) * rstd;
+        if (gg) {                                         // swish gate of Eq. 7: y * g * sigmoid(g)
+          const u32x2 gw = *(const u32x2*)(gg + mb * 32 + rq * 8 + hf * 4);
+          const float gv[4] = {__uint_as_float(gw[0] << 16), __uint_as_float(gw[0] & 0xffff0000u),
+                               __uint_as_float(gw[1] << 16), __uint_as_float(gw[1] & 0xffff0000u)};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] *= gv[e] / (1.f + __expf(-gv[e]));
+        }
+        const u32x2 w = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
         *(u32x2*)(og + mb * 32 + rq * 8 + hf * 4) = w;
       }
   }

@@ -1,6 +1,7 @@
 // Gated retention in its recurrent form (section 3.1, Eq. 5):
 //   S_n = gamma_n S_{n-1} + K_n^T V_n,   o_n = scale * Q_n S_n,
-// optionally followed by the per-head GroupNorm of Eq. 7 (no learned affine).
+// optionally followed by the per-head GroupNorm of Eq. 7 (no learned affine)
+// and the multiplication by swish(gate) of the same equation.
 // fp32 arithmetic on the vector ALU for any storage dtype and head dims up to
 // 128. It is the decode step of the self-decoder (one row per sequence, the
 // state read and written once: HBM-bound) and the prefill path of every shape
@@ -108,9 +109,17 @@ __global__ void __launch_bounds__(256) gret_recurrent_kernel(GretView a) {
       for (int r = 0; r < kRowsPerThread; ++r) out[r] = (out[r] - mean) * rstd;
     }
     if (kk == 0) {
+      const T* gate = a.gate ? (const T*)a.gate + ((size_t)b * a.T * a.H + h) * a.dv + n * a.H * a.dv : nullptr;
 #pragma unroll
       for (int r = 0; r < kRowsPerThread; ++r)
-        if (r < n_rows) Elem<T>::store(o + n * a.H * a.dv + rr + 8 * r, out[r]);
+        if (r < n_rows) {
+          float y = out[r];
+          if (gate) {                                   // swish gate of Eq. 7: y * g * sigmoid(g)
+            const float gv = Elem<T>::load(gate + rr + 8 * r);
+            y *= gv / (1.f + __expf(-gv));
+          }
+          Elem<T>::store(o + n * a.H * a.dv + rr + 8 * r, y);
+        }
     }
   }
 

@@ -315,7 +315,7 @@ int yoco_gret_prefill_workspace(int B, int64_t T, int H, int dk, int dv, int chu
   return YOCO_OK;
 }
 
-int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, void* o,
+int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* log_gamma, const void* gate, void* o,
                       const float* state_in, float* state_out, int B, int64_t T, int H, int dk, int dv, int chunk,
                       float scale, int group_norm, float eps, int dtype, void* workspace, size_t workspace_bytes,
                       void* stream) {
@@ -333,10 +333,10 @@ int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* 
     return hip_result(yoco::launch_fill_zero(state_out, nb / sizeof(float), (hipStream_t)stream), "gret_prefill");
   }
   if (!q || !k || !v || !log_gamma || !o) return fail(YOCO_ERR_INVALID_ARG, "null tensor pointer");
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (((uintptr_t)log_gamma) & 3u))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (gate && !aligned16(gate)) || (((uintptr_t)log_gamma) & 3u))
     return fail(YOCO_ERR_ALIGNMENT, "tensor pointer not aligned");
   yoco::GretView a;
-  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma; a.gate = gate;
   a.state_in = state_in; a.state_out = state_out;
   a.T = T; a.B = B; a.H = H; a.dk = dk; a.dv = dv;
   a.scale = scale; a.eps = eps; a.group_norm = group_norm != 0;
@@ -348,16 +348,17 @@ int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* 
   return hip_result(yoco::launch_gret_recurrent(a, dtype, (hipStream_t)stream), "gret_prefill");
 }
 
-int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, void* o, float* state,
+int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, const void* gate, void* o, float* state,
                      int B, int H, int dk, int dv, float scale, int group_norm, float eps, int dtype, void* stream) {
   int rc = check_gret_shape(B, 1, H, dk, dv, dtype);
   if (rc) return rc;
   if (!(eps >= 0.f)) return fail(YOCO_ERR_INVALID_ARG, "negative eps");
   if (!q || !k || !v || !log_gamma || !o || !state) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(state) || (((uintptr_t)log_gamma) & 3u))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(state) || (gate && !aligned16(gate)) ||
+      (((uintptr_t)log_gamma) & 3u))
     return fail(YOCO_ERR_ALIGNMENT, "pointer not aligned");
   yoco::GretView a;
-  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.log_gamma = log_gamma; a.gate = gate;
   a.state_in = state; a.state_out = state;
   a.T = 1; a.B = B; a.H = H; a.dk = dk; a.dv = dv;
   a.scale = scale; a.eps = eps; a.group_norm = group_norm != 0;

@@ -46,13 +46,14 @@ struct AttnView {
 
 // One gated-retention problem (section 3.1). q, k: [B,T,H,dk]; v, o: [B,T,H,dv];
 // log_gamma: [B,T,H] fp32, the natural log of the decays; states: [B,H,dv,dk]
-// fp32 (the transpose of S = K^T V), either may be null.
+// fp32 (the transpose of S = K^T V), either may be null; gate: like v, may be null.
 struct GretView {
   const void* q;
   const void* k;
   const void* v;
   void* o;
   const float* log_gamma;
+  const void* gate;          // [B,T,H,dv] or null: the output is multiplied by swish(gate) (Eq. 7)
   const float* state_in;
   float* state_out;
   int64_t T;

@@ -77,10 +77,11 @@ class YocoStack:
                 code = yb.F32 if self.dtype == torch.float32 else yb.BF16
                 nbytes = yb.gret_prefill_workspace(1, T, self.Hq, self.d, self.d, 256, code)
                 ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device) if nbytes else None
+                gate = (xn @ L["W_gate"]).to(self.dtype).view(1, T, self.Hq, self.d)
                 o = yb.gret_prefill(q, k, v, lg, self.scale, chunk=256, group_norm=True, eps=self.eps,
-                                    state_out=None if rings is None else rings[n], workspace=ws)
-                a = torch.nn.functional.silu(xn @ L["W_gate"]) * o.view(T, self.Hq * self.d).to(self.glue)
-                del ws, lg
+                                    state_out=None if rings is None else rings[n], workspace=ws, gate=gate)
+                a = o.view(T, self.Hq * self.d).to(self.glue)
+                del ws, lg, gate
             else:
                 o = yb.swa_prefill(q, k, v, self.window, self.scale)
                 if rings is not None:
@@ -200,9 +201,10 @@ class YocoStack:
             k = (xn @ L["W_K"]).to(self.dtype).view(1, self.Hkv_self, self.d)
             v = (xn @ L["W_V"]).to(self.dtype).view(1, self.Hkv_self, self.d)
             if self.self_kind == "gret":
+                gate = (xn @ L["W_gate"]).to(self.dtype).view(1, self.Hq, self.d)
                 o = yb.gret_decode(q, k, v, self._log_decay(xn, L).view(1, self.Hq), ring, self.scale, group_norm=True,
-                                   eps=self.eps)
-                a = torch.nn.functional.silu(xn @ L["W_gate"]) * o.view(1, self.Hq * self.d).to(self.glue)
+                                   eps=self.eps, gate=gate)
+                a = o.view(1, self.Hq * self.d).to(self.glue)
             else:
                 yb.kv_cache_append(ring, k, v, pos, True)
                 o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"])

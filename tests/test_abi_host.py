@@ -154,12 +154,13 @@ def test_gated_retention_calls_validate_before_launching():
     assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 256, yoco.BF16, None) == -1
 
     def prefill(q=p, k=p, v=p, g=p, o=p, s_in=None, s_out=None, B=1, T=10, H=2, dk=128, dv=128, chunk=256, eps=1e-6, dt=yoco.BF16,
-                ws=None, wsb=0):
-        return L.yoco_gret_prefill(q, k, v, g, o, s_in, s_out, B, T, H, dk, dv, chunk, 1.0, 1, eps, dt, ws, wsb, None)
+                ws=None, wsb=0, gate=None):
+        return L.yoco_gret_prefill(q, k, v, g, gate, o, s_in, s_out, B, T, H, dk, dv, chunk, 1.0, 1, eps, dt, ws, wsb, None)
     assert prefill(q=None) == -1
     assert prefill(g=None) == -1
     assert prefill(v=p + 8) == -3
     assert prefill(g=p + 2) == -3
+    assert prefill(gate=p + 8) == -3
     assert prefill(s_in=p + 4) == -3
     assert prefill(ws=p + 16, wsb=1 << 30) == -3
     assert prefill(T=-1) == -1
@@ -173,10 +174,11 @@ def test_gated_retention_calls_validate_before_launching():
     assert b"no kernel" in L.yoco_last_error_string()
     assert prefill(T=0, q=None, k=None, v=None, g=None, o=None) == 0   # empty prompt, no state to copy
 
-    def decode(q=p, k=p, v=p, g=p, o=p, st=p, B=2, H=2, dk=128, dv=128, eps=1e-6, dt=yoco.BF16):
-        return L.yoco_gret_decode(q, k, v, g, o, st, B, H, dk, dv, 1.0, 1, eps, dt, None)
+    def decode(q=p, k=p, v=p, g=p, o=p, st=p, B=2, H=2, dk=128, dv=128, eps=1e-6, dt=yoco.BF16, gate=None):
+        return L.yoco_gret_decode(q, k, v, g, gate, o, st, B, H, dk, dv, 1.0, 1, eps, dt, None)
     assert decode(st=None) == -1
     assert decode(o=p + 2) == -3
+    assert decode(gate=p + 4) == -3
     assert decode(B=0) == -1
     assert decode(dv=4) == -3
     assert decode(dt=-1) == -2

@@ -205,6 +205,12 @@ def test_rmsnorm_and_global_kv_against_library():
     assert np.abs(Ki[:, 1, :] - ref[:, 8:16]).max() < 1e-14
 
 
+def test_swish_against_library():
+    x = np.linspace(-30, 30, 241)
+    assert np.abs(oracle.swish(x) - F.silu(torch.from_numpy(x)).numpy()).max() < 1e-13
+    assert oracle.swish(0.0) == 0.0 and abs(oracle.swish(40.0) - 40.0) < 1e-12
+
+
 def test_swiglu_against_library():
     rng = np.random.default_rng(14)
     X = rng.standard_normal((5, 16))
