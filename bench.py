@@ -118,9 +118,56 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    swa_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps if args.only not in ("decode", "gret") else float("nan")
+    swa_times = sorted(a.elapsed_time(b) for a, b in evs) if args.only not in ("decode", "gret") else [float("nan")]
+    swa_ms = sum(swa_times) / len(swa_times)
     flops = swa_flops(T, H, d, C)
     swa_tflops = flops / (swa_ms * 1e-3) / 1e12
+    # the same launch with the caches flushed before it (a 512 MiB buffer is rewritten between repetitions)
+    swa_flushed = None
+    if args.only in ("all", "swa"):
+        flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        ft = []
+        for rep in range(20):
+            flush.fill_(rep & 0xff)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            yoco.swa_prefill(q, k, v, C, scale, out=o)
+            e1.record()
+            torch.cuda.synchronize()
+            ft.append(e0.elapsed_time(e1))
+        ft.sort()
+        swa_flushed = dict(ms_median=round(ft[len(ft) // 2], 4), ms_min=round(ft[0], 4))
+        del flush
+
+    # ---- what this machine can do: an MFMA-only loop and a streaming read, measured in the same run
+    ceilings = None
+    if args.only == "all":
+        g = torch.Generator(device=dev)
+        g.manual_seed(5)
+        seed_rand = torch.empty(8192, dtype=torch.float32, device=dev).normal_(0.0, 0.5, generator=g).to(torch.bfloat16)
+        seed_zero = torch.zeros(8192, dtype=torch.bfloat16, device=dev)
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+        big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        big.fill_(1)
+
+        def rate(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = sum(fn() for _ in range(reps))
+            e1.record()
+            torch.cuda.synchronize()
+            return work / (e0.elapsed_time(e1) * 1e-3)
+
+        ceilings = dict(
+            mfma_bf16_TFLOPs_random_operands=round(rate(lambda: yoco.ceiling_mfma(seed_rand, sink, 20000, 256), 3) / 1e12, 1),
+            mfma_bf16_TFLOPs_zero_operands=round(rate(lambda: yoco.ceiling_mfma(seed_zero, sink, 20000, 256), 3) / 1e12, 1),
+            stream_read_GBps=round(max(rate(lambda n=n: yoco.ceiling_stream_read(big, sink, n), 10) for n in (256, 512, 1024)) / 1e9, 1),
+            note="MFMA-only loop (2 wavefronts per SIMD, register operands) and a 2 GiB streaming read with 128-bit "
+                 "nontemporal loads (best of 1, 2 and 4 workgroups per CU)")
+        del big
+        torch.cuda.empty_cache()
 
     # ---- the decode workloads of the metric: 13 cross-decoder layers over one shared cache
     decode = {}
@@ -264,10 +311,15 @@ def main():
 
             ee_ms = timed(lambda: st.forward_early_exit(tok))
             full_ms = timed(lambda: st.forward_full(tok, rows=slice(ec["T"] - 1, ec["T"])))
-            del st, tok
+            es = ec["stack"]
+            eq = ys.device_normal((1, ec["T"], es["Hq"], es["d"]), 700, 0.5, torch.bfloat16, dev)
+            swa_layer_ms = timed(lambda: yoco.swa_prefill(eq, eq, eq, es["window"], scale))
+            del st, tok, eq
             torch.cuda.empty_cache()
         e2e = dict(T=ec["T"], early_exit_prefill_ms=round(ee_ms, 1), full_forward_ms=round(full_ms, 1),
                    early_exit_speedup=round(full_ms / ee_ms, 2), early_exit_tokens_per_s=round(ec["T"] / (ee_ms * 1e-3), 1),
+                   swa_ms_per_layer=round(swa_layer_ms, 2),
+                   swa_share_of_early_exit_prefill=round(es["n_self"] * swa_layer_ms / ee_ms, 3),
                    note="1.4B-shape random-init stack, 12 + 12 layers, bf16 torch GEMMs around libyoco's attention")
 
     # ---- the oracle on the host cores, bounded sample of the same SWA workload
@@ -292,8 +344,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "swa_prefill_32k: B=1 T=32768 24x128 heads window 1024 (+ K^/V^ write of T rows x 8 KV heads, "
                                "last-token cross-attention, one split-KV decode step)", "seed": c["seed"]},
-        "swa_prefill": {"ms": round(swa_ms, 4), "tokens_per_s": round(T / (swa_ms * 1e-3), 1),
-                        "TFLOPs": round(swa_tflops, 1), "frac_of_mfma_peak": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "swa_prefill": {"ms": round(swa_ms, 4), "ms_median": round(swa_times[len(swa_times) // 2], 4), "ms_min": round(swa_times[0], 4),
+                        "tokens_per_s": round(T / (swa_ms * 1e-3), 1),
+                        "TFLOPs": round(swa_tflops, 1), "frac_of_mfma_peak": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "caches_flushed": swa_flushed},
+        "peaks": {"mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "hbm_GBps": HBM_PEAK_GBS, "measured": ceilings},
         "roofline": {"kernel": "yoco_swa_prefill", "bound": "mfma", "achieved": round(swa_tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": int(SWA_TRAFFIC_BYTES["fetch"] + SWA_TRAFFIC_BYTES["write"]),

@@ -237,6 +237,19 @@ int yoco_gret_prefill(const void* q, const void* k, const void* v, const float* 
 int yoco_gret_decode(const void* q, const void* k, const void* v, const float* log_gamma, const void* gate, void* o, float* state,
                      int B, int H, int dk, int dv, float scale, int group_norm, float eps, int dtype, void* stream);
 
+/*
+ * ---- Measured ceilings (measurement aids for the benchmark, not part of the path) ----
+ * yoco_ceiling_mfma: `workgroups` workgroups of 8 wavefronts each issue
+ * 8 * iters back-to-back v_mfma_f32_32x32x16_bf16 (32768 flops each) on
+ * operands read once from `seed` (device, 16384 bytes: zeros and random values
+ * give different rates, the clock follows the data); flops per launch =
+ * workgroups * 8 * 8 * iters * 32768. `sink`: 4 device bytes, practically never
+ * written. yoco_ceiling_stream_read: reads `bytes` (a multiple of 16) of `buf`
+ * once with 128-bit nontemporal loads, `workgroups` contiguous shares.
+ */
+int yoco_ceiling_mfma(const void* seed, void* sink, int iters, int workgroups, void* stream);
+int yoco_ceiling_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, void* stream);
+
 /* Description of the last failure on the calling thread ("" if none). */
 const char* yoco_last_error_string(void);
 

@@ -49,7 +49,9 @@ def lib():
     L.yoco_gret_prefill_workspace.argtypes = [i32, i64, i32, i32, i32, i32, i32, C.POINTER(sz)]
     L.yoco_gret_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, f32, i32, f32, i32, vp, sz, vp]
     L.yoco_gret_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, f32, i32, vp]
-    for name in ("yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
+    L.yoco_ceiling_mfma.argtypes = [vp, vp, i32, i32, vp]
+    L.yoco_ceiling_stream_read.argtypes = [vp, sz, vp, i32, vp]
+    for name in ("yoco_ceiling_mfma", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
                  "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode",
                  "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode",
                  "yoco_gret_prefill_workspace", "yoco_gret_prefill", "yoco_gret_decode"):
@@ -256,3 +258,16 @@ def gret_decode(q, k, v, log_gamma, state, scale, group_norm=True, eps=1e-6, out
                                   _state(state, "state", B, H, dk, dv), B, H, dk, dv, scale, int(bool(group_norm)), eps,
                                   _dtype(q), _stream()))
     return o
+
+
+def ceiling_mfma(seed, sink, iters, workgroups):
+    """Launch the MFMA-only loop (yoco_ceiling_mfma); returns the flops of the launch."""
+    _check(lib().yoco_ceiling_mfma(_dev(seed, "seed"), _dev(sink, "sink"), iters, workgroups, _stream()))
+    return workgroups * 8 * 8 * iters * 32768.0
+
+
+def ceiling_stream_read(buf, sink, workgroups):
+    """Launch the streaming read of `buf` (yoco_ceiling_stream_read); returns the bytes read."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().yoco_ceiling_stream_read(_dev(buf, "buf"), nbytes, _dev(sink, "sink"), workgroups, _stream()))
+    return float(nbytes)

@@ -367,5 +367,19 @@ int yoco_gret_decode(const void* q, const void* k, const void* v, const float* l
   return hip_result(yoco::launch_gret_recurrent(a, dtype, (hipStream_t)stream), "gret_decode");
 }
 
+int yoco_ceiling_mfma(const void* seed, void* sink, int iters, int workgroups, void* stream) {
+  if (!seed || !sink) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(seed)) return fail(YOCO_ERR_ALIGNMENT, "seed not 16-byte aligned");
+  if (iters <= 0 || workgroups <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive iters or workgroups");
+  return hip_result(yoco::launch_mfma_ceiling(seed, sink, iters, workgroups, (hipStream_t)stream), "ceiling_mfma");
+}
+
+int yoco_ceiling_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, void* stream) {
+  if (!buf || !sink) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(buf) || bytes % 16) return fail(YOCO_ERR_ALIGNMENT, "buffer not 16-byte aligned or size not a multiple of 16");
+  if (bytes == 0 || workgroups <= 0) return fail(YOCO_ERR_INVALID_ARG, "empty buffer or non-positive workgroups");
+  return hip_result(yoco::launch_stream_read(buf, bytes, sink, workgroups, (hipStream_t)stream), "ceiling_stream_read");
+}
+
 }  // extern "C"
 #pragma GCC visibility pop

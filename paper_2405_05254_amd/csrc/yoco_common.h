@@ -89,6 +89,10 @@ bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
                               float* ws, int splits, void* o_direct, hipStream_t s);
 
+// Measured-ceiling microbenchmarks (ceilings.hip).
+hipError_t launch_mfma_ceiling(const void* seed, void* sink, int iters, int workgroups, hipStream_t s);
+hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s);
+
 // Partial result of one split, per (b, h, split): o[0..d), then the running max
 // m (natural-log units) and sum l, padded so every row starts 16-byte aligned.
 __host__ __device__ inline size_t partial_stride(int d) { return (size_t)d + 4; }
