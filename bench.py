@@ -357,6 +357,10 @@ def main():
         "gated_retention": gret,
         "e2e_early_exit_128k": e2e,
         "cpu_baseline": cpu,
+        # the paper's own profiling figures (section 4.4), another machine and the whole model: context, not a target
+        "paper_context": {"hardware": "H100-80GB", "model": "YOCO-3B with the gated-retention self-decoder, whole model",
+                          "prefill_512k_s": {"transformer": 180, "yoco": "< 6"}, "prefill_speedup": {"32k": 2.87, "1m": 71.8},
+                          "throughput_512k_tokens_per_s": {"transformer": 4.5, "yoco": 43.1}, "memory_1m_gb": 12.4},
     }
     print(json.dumps(out))
 
