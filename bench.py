@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes of one SWA prefill launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) of `bench.py --only swa`, each scaled by what the counter reads for a 1 GiB copy (`--only calib`:
 # FETCH_SIZE reads 0.5 GiB -> factor 2.0, WRITE_SIZE reads 1.0 GiB -> factor 1.0). See profiles/.
-SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308331.6 * 1024, "write": 1.0 * 198446.7 * 1024}
+SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308421.3 * 1024, "write": 1.0 * 198114.6 * 1024}
 
 
 def swa_flops(T, H, d, C):
@@ -352,7 +352,7 @@ def main():
         "roofline": {"kernel": "yoco_swa_prefill", "bound": "mfma", "achieved": round(swa_tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": int(SWA_TRAFFIC_BYTES["fetch"] + SWA_TRAFFIC_BYTES["write"]),
-                     "traffic_note": "HBM bytes per launch (fetch 0.631 GB + write 0.203 GB) against 0.805 GB algorithmic"},
+                     "traffic_note": "HBM bytes per launch (fetch 0.632 GB + write 0.203 GB) against 0.805 GB algorithmic"},
         "decode": decode,
         "gated_retention": gret,
         "e2e_early_exit_128k": e2e,
