@@ -198,6 +198,7 @@ DECODE_CASES = [
     ("bf16", 6, 2, 128, 600, [0, 600]),                   # an empty sequence gives zeros
     ("bf16", 10, 2, 128, 900, [900]),                     # G = 5 (no streaming fast path)
     ("bf16", 4, 2, 64, 400, [400, 13]),
+    ("bf16", 4, 2, 128, 400, [0, 400, 17]),               # one split: pass 1 stores the output itself; an empty sequence
 ]
 
 
