@@ -100,6 +100,8 @@ class KVCache:
     torch owns the memory, the descriptor is yoco_kv_cache."""
 
     def __init__(self, B, Hkv, d, N_cap, dtype=torch.bfloat16, device="cuda"):
+        if dtype not in (torch.float32, torch.bfloat16):
+            raise YocoError("unsupported cache dtype %s" % dtype)
         code = F32 if dtype == torch.float32 else BF16
         self.bytes = kv_cache_bytes(B, Hkv, d, N_cap, code)
         self.mem = torch.empty(self.bytes, dtype=torch.uint8, device=device)

@@ -50,16 +50,13 @@ int check_heads(int Hq, int Hkv) {
 // 6.0 TB/s at 2048). At least 512 rows per split.
 // YOCO_DECODE_BLOCKS overrides the workgroup target (tuning aid).
 int decode_splits(const yoco_kv_cache* c) {
-  static int cus = 0;
-  if (cus == 0) {
+  static const int cus = [] {                     // initialised once, thread-safe
     int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;               // no device visible (host-only sizing): MI355X has 256 CUs
+    const bool ok = hipGetDevice(&dev) == hipSuccess &&
+                    hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0;
     (void)hipGetLastError();
-  }
+    return ok ? n : 256;                          // no device visible (host-only sizing): MI355X has 256 CUs
+  }();
   int64_t target = cus;
   if (const char* e = getenv("YOCO_DECODE_BLOCKS")) {
     const long v = atol(e);
