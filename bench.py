@@ -204,8 +204,8 @@ def main():
                                 cache_bytes=int(cache_bytes))
             del kvc, Kp, Vp, w, qs
             torch.cuda.empty_cache()
-        # one generation step of the self-decoder: 13 layers, each appends the new row to its own rolling
-        # window cache (window 1024, 24 heads) and attends to it, 16 sequences at position 32767
+        # one generation step of the self-decoder: 13 layers, each stores the new row in its own rolling
+        # window cache (window 1024, 24 heads) and attends to it in the same launch, 16 sequences at position 32767
         sc = ys.CONFIGS["swa_prefill_32k"]
         B, Cw, Hs, layers = 16, sc["window"], sc["Hq"], 13
         rings = [yoco.KVCache(B, Hs, d, Cw, torch.bfloat16) for _ in range(layers)]
@@ -224,8 +224,7 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for i in range(layers):
-                yoco.kv_cache_append(rings[i], k_new, k_new, pos, True)
-                yoco.swa_decode(rings[i], qs[i], ln, scale, w, out=od)
+                yoco.swa_decode(rings[i], qs[i], ln, scale, w, out=od, k_new=k_new, v_new=k_new)   # stores the new row itself
             e1.record()
             torch.cuda.synchronize()
             if rep >= 2:

@@ -179,16 +179,19 @@ int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, c
 /*
  * One decode step of a self-decoder layer: Eq. 8 for one new token per
  * sequence. q, o: [B,Hq,d] of the cache dtype. lens: device int64 [B], the
- * number of tokens of sequence b so far including the new one, whose row has
- * been appended before the call (the mask includes j = i). The row attends to
+ * number of tokens of sequence b so far including the new one (the mask
+ * includes j = i). k_new, v_new: the new token's rows, [B,Hkv,d] of the cache
+ * dtype, which the call stores at slot (lens[b] - 1) mod N_cap before
+ * attending (sequences with lens[b] <= 0 store nothing); or both NULL when
+ * the rows have been appended already (yoco_kv_cache_append). The row attends to
  * the min(lens[b], N_cap) rows the ring holds, which are exactly positions
  * lens[b]-N_cap .. lens[b]-1; the order of the slots is irrelevant to a
  * softmax-weighted sum. Same two passes, workspace
  * (yoco_cross_attn_decode_workspace on this ring) and reproducibility as
  * yoco_cross_attn_decode.
  */
-int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int64_t* lens, int Hq, float scale,
-                    void* workspace, size_t workspace_bytes, void* stream);
+int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, const void* k_new, const void* v_new, void* o,
+                    const int64_t* lens, int Hq, float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * ---- Gated retention, the paper's other self-decoder module (section 3.1) ----

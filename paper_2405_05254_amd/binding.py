@@ -45,7 +45,7 @@ def lib():
     L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
     L.yoco_swa_cache_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
     L.yoco_kv_cache_append.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, i32, vp]
-    L.yoco_swa_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
+    L.yoco_swa_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, vp, vp, i32, f32, vp, sz, vp]
     L.yoco_gret_prefill_workspace.argtypes = [i32, i64, i32, i32, i32, i32, i32, C.POINTER(sz)]
     L.yoco_gret_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, f32, i32, f32, i32, vp, sz, vp]
     L.yoco_gret_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, f32, i32, vp]
@@ -191,15 +191,22 @@ def kv_cache_append(cache, k, v, pos, ring):
                                       _dtype(k), _stream()))
 
 
-def swa_decode(ring, q, lens, scale, workspace, out=None):
-    """q [B,Hq,d], lens int64 [B] (device, tokens so far including the new one) -> o [B,Hq,d] (yoco_swa_decode)."""
+def swa_decode(ring, q, lens, scale, workspace, out=None, k_new=None, v_new=None):
+    """q [B,Hq,d], lens int64 [B] (device, tokens so far including the new one) -> o [B,Hq,d] (yoco_swa_decode).
+    k_new, v_new [B,Hkv,d]: the new token's rows, stored by the same call; None when they were appended before."""
     B, Hq, d = q.shape
     if B != ring.B or d != ring.d or q.dtype != ring.dtype:
         raise YocoError("q does not match the cache")
     if lens.dtype != torch.int64 or lens.shape != (B,):
         raise YocoError("lens must be int64 [B]")
+    if (k_new is None) != (v_new is None):
+        raise YocoError("k_new and v_new go together")
+    if k_new is not None and (k_new.shape != (B, ring.Hkv, d) or v_new.shape != k_new.shape or k_new.dtype != ring.dtype
+                              or v_new.dtype != ring.dtype):
+        raise YocoError("k_new/v_new do not match the cache")
     o = torch.empty_like(q) if out is None else out
-    _check(lib().yoco_swa_decode(C.byref(ring.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq, scale,
+    _check(lib().yoco_swa_decode(C.byref(ring.desc), _dev(q, "q"), _dev(k_new, "k_new") if k_new is not None else None,
+                                 _dev(v_new, "v_new") if v_new is not None else None, _dev(o, "o"), _dev(lens, "lens"), Hq, scale,
                                  _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
     return o
 

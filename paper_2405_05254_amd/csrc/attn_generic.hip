@@ -279,12 +279,12 @@ __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S*
 }
 
 // One row per sequence at a device-side position: k, v [B,Hkv,d]; sequence b's
-// row goes to slot pos[b] (ring: modulo N_cap). Out-of-range positions write
+// row goes to slot pos[b] + bias (ring: modulo N_cap). Out-of-range positions write
 // nothing.
 template <typename S, typename D>
 __global__ void __launch_bounds__(256) kv_append_kernel(yoco_kv_cache c, const S* __restrict__ k,
                                                         const S* __restrict__ v, const int64_t* __restrict__ pos,
-                                                        int ring) {
+                                                        int64_t bias, int ring) {
   const int d8 = c.d / 8;
   const int64_t total = (int64_t)c.B * c.Hkv * d8;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -292,7 +292,7 @@ __global__ void __launch_bounds__(256) kv_append_kernel(yoco_kv_cache c, const S
     const int e8 = (int)(idx % d8);
     const int g = (int)((idx / d8) % c.Hkv);
     const int b = (int)(idx / ((int64_t)d8 * c.Hkv));
-    int64_t slot = pos[b];
+    int64_t slot = pos[b] + bias;
     if (slot < 0) continue;
     if (slot >= c.N_cap) {
       if (!ring) continue;
@@ -325,20 +325,20 @@ hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v,
   return hipGetLastError();
 }
 
-hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int ring,
+hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int64_t bias, int ring,
                             int src_dtype, hipStream_t s) {
   const int64_t total = (int64_t)c.B * c.Hkv * (c.d / 8);
   int64_t blocks = (total + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   dim3 grid((unsigned)blocks), block(256);
   if (src_dtype == YOCO_F32 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_append_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, ring);
+    hipLaunchKernelGGL((kv_append_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, bias, ring);
   else if (src_dtype == YOCO_F32 && c.dtype == YOCO_BF16)
-    hipLaunchKernelGGL((kv_append_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, ring);
+    hipLaunchKernelGGL((kv_append_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, pos, bias, ring);
   else if (src_dtype == YOCO_BF16 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_append_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, ring);
+    hipLaunchKernelGGL((kv_append_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, bias, ring);
   else
-    hipLaunchKernelGGL((kv_append_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, ring);
+    hipLaunchKernelGGL((kv_append_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, pos, bias, ring);
   return hipGetLastError();
 }
 

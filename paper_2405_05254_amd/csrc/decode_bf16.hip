@@ -98,10 +98,15 @@ __device__ __forceinline__ void step(State<G>& st, const u32x4 (&kq)[G], const u
   }
 }
 
-template <int G, int R>
+// APPEND: the call also stores the new token's K/V row (k_new, v_new: [B,Hkv,128]) at slot lens[b] - 1 (modulo
+// the capacity for a rolling cache) and attends to it. The row is taken from registers wherever the stream
+// meets its slot, so nothing is read back that this launch writes.
+template <int G, int R, bool APPEND>
 __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
                                                           const int64_t* __restrict__ lens, int64_t fixed_len, int Hq, float scale_log2,
-                                                          float* __restrict__ ws, int splits, bf16_t* __restrict__ o_direct) {
+                                                          float* __restrict__ ws, int splits, bf16_t* __restrict__ o_direct,
+                                                          const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+                                                          int ring) {
   constexpr int kRowsPerStep = 4 * R;
   __shared__ float red_o[4][G][kD];
   __shared__ float red_ml[4][G][2];
@@ -109,8 +114,8 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane >> 4, seg = lane & 15;
 
-  int64_t len = lens ? lens[b] : fixed_len;         // a host-known length serves the few-row prefill case
-  len = len < 0 ? 0 : (len > c.N_cap ? c.N_cap : len);
+  const int64_t len_raw = lens ? lens[b] : fixed_len;   // a host-known length serves the few-row prefill case
+  const int64_t len = len_raw < 0 ? 0 : (len_raw > c.N_cap ? c.N_cap : len_raw);
   const int64_t chunk = (((len + splits - 1) / splits) + 127) & ~(int64_t)127;  // rows per split, 128 | chunk
   const int64_t j_lo = sp * chunk;
   const int64_t j_hi = (j_lo + chunk < len) ? j_lo + chunk : len;
@@ -136,6 +141,19 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
   const u32x4* kp = (const u32x4*)c.k + plane + seg;
   const u32x4* vp = (const u32x4*)c.v + plane + seg;
 
+  int64_t slot = -1;                                   // where the new row goes (APPEND), -1 = nowhere
+  u32x4 knew = {0, 0, 0, 0}, vnew = knew;
+  if (APPEND) {
+    const int64_t pos = len_raw - 1;
+    if (pos >= 0 && (ring || pos < c.N_cap)) slot = pos >= c.N_cap ? pos % c.N_cap : pos;
+    knew = *(const u32x4*)(k_new + ((int64_t)b * c.Hkv + g) * kD + seg * 8);
+    vnew = *(const u32x4*)(v_new + ((int64_t)b * c.Hkv + g) * kD + seg * 8);
+    if (slot >= j_lo && slot < j_hi && wave == 0 && lane < 32) {      // the split that owns the slot stores the row
+      u32x4* dst = (u32x4*)(lane < 16 ? c.k : c.v) + plane + slot * (kD / 8) + seg;
+      *dst = lane < 16 ? knew : vnew;
+    }
+  }
+
   if (w_lo < w_hi) {
     const int64_t last = w_hi - 1;
     u32x4 kn[R], vn[R];
@@ -146,6 +164,10 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
         row = row < last ? row : last;                 // clamped rows are masked in the tail step
         kn[u] = __builtin_nontemporal_load(kp + row * (kD / 8));
         vn[u] = __builtin_nontemporal_load(vp + row * (kD / 8));
+        if (APPEND && row == slot) {                   // the new row comes from the registers, not from memory
+          kn[u] = knew;
+          vn[u] = vnew;
+        }
       }
     };
     load(w_lo);
@@ -217,19 +239,28 @@ bool decode_bf16_supported(const yoco_kv_cache& c, int Hq) {
 }
 
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
-                              float* ws, int splits, void* o_direct, hipStream_t s) {
+                              float* ws, int splits, void* o_direct, const void* k_new, const void* v_new, int ring,
+                              hipStream_t s) {
   bf16_t* od = splits == 1 ? (bf16_t*)o_direct : nullptr;
   dim3 grid(splits, c.Hkv, c.B), block(256);
   const float sl2 = scale * kLog2e;
   const bf16_t* qp = (const bf16_t*)q;
   constexpr int R = 8;
+  const bf16_t* kn = (const bf16_t*)k_new;
+  const bf16_t* vn = (const bf16_t*)v_new;
+#define YOCO_DECODE_LAUNCH(G)                                                                                                   \
+  if (kn)                                                                                                                       \
+    hipLaunchKernelGGL((decode_bf16_kernel<G, R, true>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od, kn, vn, ring); \
+  else                                                                                                                          \
+    hipLaunchKernelGGL((decode_bf16_kernel<G, R, false>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od, kn, vn, ring);
   switch (Hq / c.Hkv) {
-    case 1: hipLaunchKernelGGL((decode_bf16_kernel<1, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 2: hipLaunchKernelGGL((decode_bf16_kernel<2, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 3: hipLaunchKernelGGL((decode_bf16_kernel<3, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 4: hipLaunchKernelGGL((decode_bf16_kernel<4, R>), grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
+    case 1: YOCO_DECODE_LAUNCH(1) break;
+    case 2: YOCO_DECODE_LAUNCH(2) break;
+    case 3: YOCO_DECODE_LAUNCH(3) break;
+    case 4: YOCO_DECODE_LAUNCH(4) break;
     default: return hipErrorInvalidValue;
   }
+#undef YOCO_DECODE_LAUNCH
   return hipGetLastError();
 }
 

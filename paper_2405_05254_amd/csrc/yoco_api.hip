@@ -73,14 +73,22 @@ int decode_splits(const yoco_kv_cache* c) {
 
 // Split-KV attention of one query token per sequence of `c`: pass 1 + merge.
 // `lens` (device) or, when it is null, `fixed_len` (host) gives the visible rows.
+// k_new / v_new (both null or both rows [B,Hkv,d] of the cache dtype): the new token's row is stored at slot
+// lens[b] - 1 (ring: modulo the capacity) by the same call and attended to.
 int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
-               float* ws, int splits, hipStream_t s, const char* what) {
+               float* ws, int splits, hipStream_t s, const char* what, const void* k_new = nullptr, const void* v_new = nullptr,
+               int ring = 0) {
   hipError_t e;
   if (yoco::decode_bf16_supported(c, Hq)) {
-    e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, o, s);
+    e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, o, k_new, v_new, ring, s);
     if (splits == 1) return hip_result(e, what);      // one split: pass 1 wrote the output
-  } else
+  } else {
+    if (k_new) {                                      // no fused path for this shape: append, then attend
+      e = yoco::launch_kv_append(c, k_new, v_new, lens, -1, ring, c.dtype, s);
+      if (e != hipSuccess) return hip_result(e, what);
+    }
     e = yoco::launch_decode_generic(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
+  }
   if (e != hipSuccess) return hip_result(e, what);
   return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, c.dtype, s), what);
 }
@@ -199,7 +207,7 @@ int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, c
   if (!k || !v || !pos) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
   if (((uintptr_t)pos) & 7u) return fail(YOCO_ERR_ALIGNMENT, "pos is not 8-byte aligned");
-  return hip_result(yoco::launch_kv_append(*c, k, v, pos, ring, src_dtype, (hipStream_t)stream), "kv_cache_append");
+  return hip_result(yoco::launch_kv_append(*c, k, v, pos, 0, ring, src_dtype, (hipStream_t)stream), "kv_cache_append");
 }
 
 int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0, int64_t Tq, int Hq,
@@ -282,8 +290,8 @@ int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const
   return run_decode(*c, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "cross_attn_decode");
 }
 
-int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int64_t* lens, int Hq, float scale,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, const void* k_new, const void* v_new, void* o,
+                    const int64_t* lens, int Hq, float scale, void* workspace, size_t workspace_bytes, void* stream) {
   // The ring holds exactly the rows the window admits and a softmax-weighted
   // sum does not depend on the order of its terms, so a decode step over the
   // ring, with lens clamped to its capacity (the kernels do), is Eq. 8.
@@ -295,12 +303,14 @@ int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, void* o, const int
   if (!aligned16(q) || !aligned16(o) || !aligned16(workspace))
     return fail(YOCO_ERR_ALIGNMENT, "pointer not 16-byte aligned");
   if (ring->B > 65535) return fail(YOCO_ERR_UNSUPPORTED, "B %d exceeds the grid limit", ring->B);
+  if ((k_new == nullptr) != (v_new == nullptr)) return fail(YOCO_ERR_INVALID_ARG, "k_new and v_new must both be given or both be null");
+  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return fail(YOCO_ERR_ALIGNMENT, "new row pointer not 16-byte aligned");
   size_t need = 0;
   int splits = 0;
   rc = yoco_cross_attn_decode_workspace(ring, Hq, &need, &splits);
   if (rc) return rc;
   if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
-  return run_decode(*ring, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "swa_decode");
+  return run_decode(*ring, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "swa_decode", k_new, v_new, 1);
 }
 
 int yoco_gret_prefill_workspace(int B, int64_t T, int H, int dk, int dv, int chunk, int dtype, size_t* bytes) {

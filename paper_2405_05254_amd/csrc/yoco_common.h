@@ -70,8 +70,8 @@ hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, i
                                hipStream_t s);
 hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t r0,
                            int64_t n, int src_dtype, hipStream_t s);
-hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int ring,
-                            int src_dtype, hipStream_t s);
+hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int64_t bias, int ring,
+                            int src_dtype, hipStream_t s);   // slot = pos[b] + bias
 
 bool gret_recurrent_supported(const GretView& a);
 hipError_t launch_gret_recurrent(const GretView& a, int dtype, hipStream_t s);
@@ -86,8 +86,10 @@ bool swa_mfma_supported(const AttnView& a, int dtype);
 hipError_t launch_swa_mfma(const AttnView& a, hipStream_t s);
 bool decode_bf16_supported(const yoco_kv_cache& c, int Hq);
 // With one split and a non-null o_direct the kernel normalises and stores the output itself (no merge pass).
+// k_new / v_new ([B,Hkv,128] bf16, or null): also store and attend to the new token's row at slot lens[b] - 1.
 hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
-                              float* ws, int splits, void* o_direct, hipStream_t s);
+                              float* ws, int splits, void* o_direct, const void* k_new, const void* v_new, int ring,
+                              hipStream_t s);
 
 // Measured-ceiling microbenchmarks (ceilings.hip).
 hipError_t launch_mfma_ceiling(const void* seed, void* sink, int iters, int workgroups, hipStream_t s);

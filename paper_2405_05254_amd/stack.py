@@ -206,8 +206,7 @@ class YocoStack:
                                    eps=self.eps, gate=gate)
                 a = o.view(1, self.Hq * self.d).to(self.glue)
             else:
-                yb.kv_cache_append(ring, k, v, pos, True)
-                o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"])
+                o = yb.swa_decode(ring, q, lens, self.scale, state["ws_ring"], k_new=k, v_new=v)   # appends the row itself
                 a = o.view(1, self.Hq * self.d).to(self.glue)
             y = a @ L["W_O"] + x
             x = _swiglu(_rmsnorm(y, L["ln2"], self.eps), L) + y

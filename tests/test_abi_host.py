@@ -133,10 +133,12 @@ def test_generation_calls_validate_before_launching():
     # swa_decode
     n, s = C.c_size_t(), C.c_int()
     assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(n), C.byref(s)) == 0
-    assert L.yoco_swa_decode(C.byref(d), p, p, p, 4, 1.0, p, n.value - 1, None) == -4
-    assert L.yoco_swa_decode(C.byref(d), p, p, p, 3, 1.0, p, n.value, None) == -1       # Hq % Hkv
-    assert L.yoco_swa_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
-    assert L.yoco_swa_decode(C.byref(d), p, p, p, 4, 1.0, p + 1, n.value, None) == -3
+    assert L.yoco_swa_decode(C.byref(d), p, None, None, p, p, 4, 1.0, p, n.value - 1, None) == -4
+    assert L.yoco_swa_decode(C.byref(d), p, None, None, p, p, 3, 1.0, p, n.value, None) == -1       # Hq % Hkv
+    assert L.yoco_swa_decode(C.byref(d), p, None, None, p, None, 4, 1.0, p, n.value, None) == -1
+    assert L.yoco_swa_decode(C.byref(d), p, None, None, p, p, 4, 1.0, p + 1, n.value, None) == -3
+    assert L.yoco_swa_decode(C.byref(d), p, p, None, p, p, 4, 1.0, p, n.value, None) == -1          # k_new without v_new
+    assert L.yoco_swa_decode(C.byref(d), p, p, p + 8, p, p, 4, 1.0, p, n.value, None) == -3
 
 
 def test_gated_retention_calls_validate_before_launching():

@@ -102,11 +102,13 @@ DECODE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,C,lens", DECODE_CASES)
-def test_swa_decode_matches_oracle(yoco, dtype, Hq, Hkv, d, C, lens):
+def test_swa_decode_matches_oracle(yoco, dtype, Hq, Hkv, d, C, lens, fused):
     """History of each sequence written through the ring in two pieces (a bulk
-    write, then the last row by a batched append), one decode step, and the
-    oracle's Eq. 8 row over the full history."""
+    write, then the last row by a batched append, or by the decode call itself
+    when `fused`), one decode step, and the oracle's Eq. 8 row over the full
+    history; the ring's slots afterwards hold the same bits either way."""
     B, Tmax = len(lens), max(lens)
     scale = 1.0 / math.sqrt(d)
     rng = np.random.default_rng(len(lens) * 100 + C)
@@ -121,11 +123,18 @@ def test_swa_decode_matches_oracle(yoco, dtype, Hq, Hkv, d, C, lens):
             yoco.swa_cache_write(ring, dev(K[b, :n - 1], dtype), dev(V[b, :n - 1], dtype), b, 0)
     last = np.stack([K[b, n - 1] for b, n in enumerate(lens)]), np.stack([V[b, n - 1] for b, n in enumerate(lens)])
     ln = torch.tensor(lens, dtype=torch.int64, device="cuda")
-    yoco.kv_cache_append(ring, dev(last[0], dtype), dev(last[1], dtype), ln - 1, True)
     nbytes, splits = yoco.cross_attn_decode_workspace(ring, Hq)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    o = yoco.swa_decode(ring, dev(q, dtype), ln, scale, ws)
+    if fused:
+        o = yoco.swa_decode(ring, dev(q, dtype), ln, scale, ws, k_new=dev(last[0], dtype), v_new=dev(last[1], dtype))
+    else:
+        yoco.kv_cache_append(ring, dev(last[0], dtype), dev(last[1], dtype), ln - 1, True)
+        o = yoco.swa_decode(ring, dev(q, dtype), ln, scale, ws)
     torch.cuda.synchronize()
+    Kp, Vp = ring.planes()
+    for b, n in enumerate(lens):                          # the new row is where an append would have put it
+        assert np.array_equal(Kp[b, :, (n - 1) % C].float().cpu().numpy(), ys.round_to(K[b, n - 1], dtype))
+        assert np.array_equal(Vp[b, :, (n - 1) % C].float().cpu().numpy(), ys.round_to(V[b, n - 1], dtype))
     got = host(o)
     ref = np.empty_like(got)
     for b, n in enumerate(lens):
