@@ -20,6 +20,10 @@ paper's own statement that the parallel, recurrent and chunkwise forms give the
 same result (also across a split of the sequence with a carried state), by
 the closed forms gamma = 1 (causal prefix sums) and gamma -> 0 (only the
 diagonal term), and GroupNorm by torch's group_norm.
+The 8-bit cache codes are pinned by the half-step error property, the
+extremes (the largest element gets +-127, a zero row gets zeros), sign and
+power-of-two scaling symmetries, torch's per-channel quantiser as a library
+routine, and the attention over them by its derived error bound.
 No function here is "parity unpinned".
 
 Readings of points the paper leaves open:
@@ -340,6 +344,57 @@ def mhgr(X, W_Q, W_K, W_V, W_gamma, W_G, W_O, H, tau, scale, eps=1e-6):
     Y = group_norm_heads(gret_parallel(Q, K, V, gret_decay(X, W_gamma, tau), scale), eps).reshape(T, -1)
     a = X @ np.asarray(W_G, F64)
     return ((a / (1.0 + np.exp(-a))) * Y) @ np.asarray(W_O, F64)
+
+
+# ---------------------------------------------------------------- 8-bit global cache
+def kv_quantise_int8(X):
+    """Symmetric 8-bit codes of cache rows, one scale per (row, KV head).
+
+    The paper only names 8-bit KV quantisation as the common remedy for cache
+    size (section 1, the 65B example) and gives no scheme; this is the plain
+    absmax one. For a row x of d numbers, all arithmetic in float32 because a
+    rounding decides the integer:  a = max|x|,  scale = a / 127,
+    code_e = round-half-even(x_e * (127 / a)) in [-127, 127]; a zero row has
+    scale 0 and codes 0. X [..., d] -> (codes int8 [..., d], scale float32 [...]).
+    """
+    X = np.asarray(X, dtype=np.float32)
+    a = np.abs(X).max(axis=-1)
+    pos = a > 0
+    safe = np.where(pos, a, np.float32(1))
+    inv = np.where(pos, np.float32(127) / safe, np.float32(0)).astype(np.float32)
+    scale = np.where(pos, a / np.float32(127), np.float32(0)).astype(np.float32)
+    y = (X * inv[..., None]).astype(np.float32)
+    codes = np.clip(np.rint(y), -127, 127).astype(np.int8)
+    return codes, scale
+
+
+def kv_dequantise_int8(codes, scale):
+    """The values an 8-bit cache stands for: code * scale, exact in float64."""
+    return np.asarray(codes, dtype=F64) * np.asarray(scale, dtype=F64)[..., None]
+
+
+def cross_attn_int8(Q, Khat, Vhat, q_pos0, scale):
+    """Eq. 3 over a cache that stores K^ and V^ as 8-bit codes: the rows are
+    quantised when written and attention runs on the values the codes stand for."""
+    Kq = kv_dequantise_int8(*kv_quantise_int8(Khat))
+    Vq = kv_dequantise_int8(*kv_quantise_int8(Vhat))
+    return cross_attn(Q, Kq, Vq, q_pos0, scale)
+
+
+def cross_attn_int8_error_bound(Q, Khat, Vhat, scale):
+    """An upper bound on |cross_attn_int8 - cross_attn| for every output element.
+
+    Every element of a row moves by at most half a code step, h = max|row|/254
+    (plus float32 rounding of the scale, covered by the 1.001). A score moves by
+    at most D = scale * max_i ||q_i||_1 * max_j h(k_j); each softmax weight then
+    changes by a factor within exp(+-2D), and the output is a convex combination
+    of V rows, so the total is  max_j h(v_j) + (exp(2D) - 1) * max|V^|.
+    """
+    Q = np.asarray(Q, dtype=F64)
+    hk = 1.001 * np.abs(np.asarray(Khat, dtype=F64)).max() / 254.0
+    hv = 1.001 * np.abs(np.asarray(Vhat, dtype=F64)).max() / 254.0
+    D = scale * np.abs(Q).sum(axis=-1).max() * hk
+    return hv + np.expm1(2.0 * D) * (np.abs(np.asarray(Vhat, dtype=F64)).max() + hv)
 
 
 def kv_cache_bytes_per_token(Hkv, d, elem_bytes, cached_layers=1):

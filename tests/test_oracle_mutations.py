@@ -218,3 +218,66 @@ GRET_MUTANTS = {
 def test_pins_catch_planted_gret_mistake(name):
     which, kw = GRET_MUTANTS[name]
     assert not gret_battery(make_gret(**kw)[which]), name
+
+
+# ---------------------------------------------------------------- 8-bit cache codes
+def make_quantiser(levels=127.0, rounding=np.rint, axis=-1, clip=127, scale_levels=127.0):
+    """A copy of the oracle's absmax quantiser with switches for planted mistakes."""
+    def quant(X):
+        X = np.asarray(X, dtype=np.float32)
+        a = np.abs(X).max(axis=axis, keepdims=True)
+        safe = np.where(a > 0, a, np.float32(1))
+        inv = np.where(a > 0, np.float32(levels) / safe, np.float32(0)).astype(np.float32)
+        scale = np.where(a > 0, a / np.float32(scale_levels), np.float32(0)).astype(np.float32)
+        codes = np.clip(rounding((X * inv).astype(np.float32)), -clip, clip).astype(np.int8)
+        if axis != -1:                                   # one scale per column of a row block, handed to every row
+            scale = np.broadcast_to(scale.max(axis=-1, keepdims=True), X.shape[:-1] + (1,))
+        return codes, np.ascontiguousarray(scale[..., 0])
+    return quant
+
+
+def quantiser_battery(quant):
+    """True if `quant` passes the pins of the real quantiser (half-step property, extremes, oddness, ties)."""
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((30, 2, 64)).astype(np.float32)
+    X *= np.exp2(rng.integers(-10, 10, size=(30, 2))).astype(np.float32)[..., None]
+    codes, scale = quant(X)
+    if scale.shape != (30, 2) or np.abs(codes.astype(np.int32)).max() > 127:
+        return False
+    a = np.abs(X).max(axis=-1).astype(np.float64)
+    if np.abs(scale.astype(np.float64) / (a / 127.0) - 1).max() > 1e-6:
+        return False
+    err = np.abs(codes.astype(np.float64) * scale.astype(np.float64)[..., None] - X)
+    if np.any(err > 0.5 * scale.astype(np.float64)[..., None] * (1 + 1e-5)):
+        return False
+    cn, _ = quant(-X)
+    if not np.array_equal(cn, -codes):
+        return False
+    ties = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]], dtype=np.float32)
+    return quant(ties)[0].tolist() == [[127, 0, 2, 2, 0, -2, -2, 126]]
+
+
+QUANT_MUTANTS = {
+    "128 levels": dict(levels=128.0, clip=128, scale_levels=128.0),
+    "codes use 128, scale uses 127": dict(levels=128.0),
+    "truncation": dict(rounding=np.trunc),
+    "floor": dict(rounding=np.floor),
+    "round half away from zero": dict(rounding=lambda y: np.sign(y) * np.floor(np.abs(y) + 0.5)),
+    "scale over the heads axis": dict(axis=-2),
+    "clip at 126": dict(clip=126),
+}
+
+
+def test_the_unmutated_quantiser_and_the_oracle_pass():
+    assert quantiser_battery(make_quantiser())
+    assert quantiser_battery(oracle.kv_quantise_int8)
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((9, 3, 32)).astype(np.float32)
+    c0, s0 = make_quantiser()(X)
+    c1, s1 = oracle.kv_quantise_int8(X)
+    assert np.array_equal(c0, c1) and np.array_equal(s0, s1)
+
+
+@pytest.mark.parametrize("name", sorted(QUANT_MUTANTS))
+def test_pins_catch_planted_quantiser_mistake(name):
+    assert not quantiser_battery(make_quantiser(**QUANT_MUTANTS[name])), name

@@ -7,6 +7,7 @@ silu), closed forms, locality/causality invariants, the GQA replication
 invariant, the early-exit and prefix invariants of the stack (Fig. 3), and the
 cache-size numbers the paper does print (tests/golden/kv_cache_tokens_per_gb.txt).
 """
+import math
 import os
 
 import numpy as np
@@ -492,3 +493,94 @@ def test_gret_stack_early_exit_prefix_and_generation_invariants():
     # and it is a different model from the sliding-window variant with the same shared matrices
     w_swa = ys.stack_weights(3, dict(SMALL, Hkv_self=4), "f32")
     assert np.abs(oracle.yoco_stack(tok, w_swa, "full") - oracle.yoco_stack(tok, ys.stack_weights(3, GRET_SMALL, "f32"), "full")).max() > 1e-4
+
+
+# ---------------------------------------------------------------- 8-bit cache codes (section 1 names 8-bit KV quantisation)
+def _rows(seed, shape, spread=True):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal(shape).astype(np.float32)
+    if spread:      # rows of very different magnitude: a scale taken over the wrong axis cannot pass
+        X *= np.exp2(rng.integers(-12, 12, size=shape[:-1])).astype(np.float32)[..., None]
+    return X
+
+
+def test_int8_codes_half_step_property_and_extremes():
+    X = _rows(0, (50, 3, 128))
+    X[7, 1] = 0.0
+    codes, scale = oracle.kv_quantise_int8(X)
+    assert codes.dtype == np.int8 and scale.dtype == np.float32 and scale.shape == X.shape[:-1]
+    assert codes.min() >= -127 and codes.max() <= 127
+    a = np.abs(X).max(axis=-1)
+    # the scale is max|row| / 127 and the largest element sits on the last code
+    np.testing.assert_allclose(scale.astype(np.float64), a.astype(np.float64) / 127.0, rtol=1e-6)
+    top = np.take_along_axis(codes, np.abs(X).argmax(axis=-1)[..., None], axis=-1)[..., 0]
+    nz = a > 0
+    assert np.all(np.abs(top[nz]) == 127)
+    assert np.all(codes[7, 1] == 0) and scale[7, 1] == 0
+    # nearest code: no element is further than half a step (plus float32 rounding) from its value
+    err = np.abs(oracle.kv_dequantise_int8(codes, scale) - X.astype(np.float64))
+    assert np.all(err <= 0.5 * scale.astype(np.float64)[..., None] * (1 + 1e-5))
+    # and half a step is reached: the rounding is to nearest, not towards zero (whose error reaches a full step)
+    assert (err / np.maximum(scale.astype(np.float64)[..., None], 1e-300)).max() > 0.49
+
+
+def test_int8_codes_symmetries():
+    X = _rows(1, (40, 2, 64))
+    codes, scale = oracle.kv_quantise_int8(X)
+    cn, sn = oracle.kv_quantise_int8(-X)
+    assert np.array_equal(cn, -codes) and np.array_equal(sn, scale)            # odd in x: round-half-even, no offset
+    c8, s8 = oracle.kv_quantise_int8(X * np.float32(8.0))
+    assert np.array_equal(c8, codes) and np.array_equal(s8, scale * np.float32(8.0))   # powers of two are exact in float32
+    # a row does not depend on the other rows or heads
+    Y = X.copy()
+    Y[3, 0] *= 100.0
+    cy, sy = oracle.kv_quantise_int8(Y)
+    keep = np.ones(X.shape[:-1], bool)
+    keep[3, 0] = False
+    assert np.array_equal(cy[keep], codes[keep]) and np.array_equal(sy[keep], scale[keep])
+
+
+def test_int8_codes_exact_on_representable_rows_and_ties():
+    # a row that is already integer codes times a power of two comes back unchanged
+    rng = np.random.default_rng(2)
+    c = rng.integers(-127, 128, size=(16, 32)).astype(np.int8)
+    c[:, 0] = 127
+    X = c.astype(np.float32) * np.float32(2.0 ** -5) * np.float32(127.0) / np.float32(127.0)
+    codes, scale = oracle.kv_quantise_int8(X)
+    assert np.array_equal(codes, c)
+    # halves round to the even neighbour: with max 127 the multiplier is exactly 1
+    X = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]], dtype=np.float32)
+    codes, scale = oracle.kv_quantise_int8(X)
+    assert codes.tolist() == [[127, 0, 2, 2, 0, -2, -2, 126]] and scale[0] == 1.0
+
+
+def test_int8_codes_against_library_quantiser():
+    X = _rows(3, (64, 128))
+    codes, scale = oracle.kv_quantise_int8(X)
+    q = torch.quantize_per_channel(torch.from_numpy(X), torch.from_numpy(scale.astype(np.float64)),
+                                   torch.zeros(64, dtype=torch.int64), 0, torch.qint8)
+    lib = q.int_repr().numpy()
+    # the library multiplies by 1/scale, the oracle by 127/max: the two may differ by one code on a rare near-tie
+    diff = np.abs(lib.astype(np.int32) - codes.astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).sum() <= 3
+    np.testing.assert_allclose(q.dequantize().numpy()[diff == 0], oracle.kv_dequantise_int8(codes, scale)[diff == 0], rtol=1e-6)
+
+
+def test_cross_attn_int8_is_attention_over_the_coded_rows_and_within_its_bound():
+    T, Hq, Hkv, d = 96, 4, 2, 32
+    scale = 1.0 / math.sqrt(d)
+    q, k, v = ys.qkv(4, T, Hq, Hkv, d, 1.0, "f32")
+    exact = oracle.cross_attn(q[-3:], k, v, T - 3, scale)
+    coded = oracle.cross_attn_int8(q[-3:], k, v, T - 3, scale)
+    err = np.abs(coded - exact).max()
+    bound = oracle.cross_attn_int8_error_bound(q[-3:], k, v, scale)
+    assert 0 < err <= bound, (err, bound)
+    # the codes, not the originals, are what is attended to: replacing K^, V^ by their coded values changes nothing
+    kq = oracle.kv_dequantise_int8(*oracle.kv_quantise_int8(k)).astype(np.float32)
+    vq = oracle.kv_dequantise_int8(*oracle.kv_quantise_int8(v)).astype(np.float32)
+    again = oracle.cross_attn_int8(q[-3:], kq, vq, T - 3, scale)
+    np.testing.assert_allclose(again, coded, rtol=0, atol=1e-6)
+    # a coarser grid (every second code) must violate the bound's leading term scaling: error grows about 2x
+    k2, s2 = oracle.kv_quantise_int8(k)
+    coarse = oracle.cross_attn(q[-3:], (2 * np.rint(k2 / 2.0)) * s2.astype(np.float64)[..., None], vq, T - 3, scale)
+    assert np.abs(coarse - exact).max() > err
