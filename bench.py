@@ -173,13 +173,20 @@ def main():
     decode = {}
     if not args.no_decode and args.only != "gret":
         del q, k, v, o
-        for name in ("decode_b16_32k", "decode_b1_512k"):
-            dc = ys.CONFIGS[name]
+        for name in ("decode_b16_32k", "decode_b1_512k", "decode_b16_32k_int8", "decode_b1_512k_int8"):
+            coded = name.endswith("_int8")                       # the same workload over the 8-bit cache
+            dc = ys.CONFIGS[name[:-5] if coded else name]
             B, N, Hq, Hkv, layers = dc["B"], dc["N"], dc["Hq"], dc["Hkv"], dc["layers"]
-            kvc = yoco.KVCache(B, Hkv, d, N, torch.bfloat16)
-            Kp, Vp = kvc.planes()
-            Kp.copy_(ys.device_normal(Kp.shape, dc["seed"], dc["std"], torch.bfloat16, dev))
-            Vp.copy_(ys.device_normal(Vp.shape, dc["seed"] + 1, dc["std"], torch.bfloat16, dev))
+            kvc = yoco.KVCache(B, Hkv, d, N, torch.int8 if coded else torch.bfloat16)
+            if coded:
+                for b in range(B):                               # rows are coded by the library's own write call
+                    yoco.global_kv_write(kvc, ys.device_normal((N, Hkv, d), dc["seed"] + 2 * b, dc["std"], torch.bfloat16, dev),
+                                         ys.device_normal((N, Hkv, d), dc["seed"] + 2 * b + 1, dc["std"], torch.bfloat16, dev), b, 0)
+            else:
+                Kp, Vp = kvc.planes()
+                Kp.copy_(ys.device_normal(Kp.shape, dc["seed"], dc["std"], torch.bfloat16, dev))
+                Vp.copy_(ys.device_normal(Vp.shape, dc["seed"] + 1, dc["std"], torch.bfloat16, dev))
+                del Kp, Vp
             qs = [ys.device_normal((B, Hq, d), 100 + i, dc["std"], torch.bfloat16, dev) for i in range(layers)]
             od = torch.empty_like(qs[0])
             ln = torch.full((B,), N, dtype=torch.int64, device=dev)
@@ -197,12 +204,14 @@ def main():
                 if rep >= 2:
                     times.append(e0.elapsed_time(e1))
             ms = sum(times) / len(times)
-            cache_bytes = 2.0 * B * N * Hkv * d * 2
+            cache_bytes = 2.0 * B * N * Hkv * (d + 4 if coded else d * 2)     # codes + one fp32 scale per row, or bf16
             gbs = layers * cache_bytes / (ms * 1e-3) / 1e9
             decode[name] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4), min_ms=round(min(times), 4),
                                 GBps=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4), splits=splits,
                                 cache_bytes=int(cache_bytes))
-            del kvc, Kp, Vp, w, qs
+            if coded:
+                decode[name]["speedup_over_bf16_cache"] = round(decode[name[:-5]]["ms_per_13_layers"] / ms, 3)
+            del kvc, w, qs
             torch.cuda.empty_cache()
         # one generation step of the self-decoder: 13 layers, each stores the new row in its own rolling
         # window cache (window 1024, 24 heads) and attends to it in the same launch, 16 sequences at position 32767

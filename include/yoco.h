@@ -62,7 +62,11 @@ typedef enum yoco_status {
   YOCO_ERR_HIP = -5          /* the HIP runtime refused a launch */
 } yoco_status;
 
-typedef enum yoco_dtype { YOCO_F32 = 0, YOCO_BF16 = 1 } yoco_dtype;
+typedef enum yoco_dtype {
+  YOCO_F32 = 0,
+  YOCO_BF16 = 1,
+  YOCO_INT8 = 2 /* only as the dtype of a global cache, see below */
+} yoco_dtype;
 
 /*
  * Descriptor of the global KV cache (section 2.2: one K^/V^ pair per sequence,
@@ -82,7 +86,29 @@ typedef struct yoco_kv_cache {
   int64_t N_cap;    /* rows per sequence the planes can hold */
 } yoco_kv_cache;
 
-/* Bytes the cache needs: 2 * B * Hkv * N_cap * d * sizeof(dtype). Host only. */
+/*
+ * The 8-bit global cache (dtype YOCO_INT8; section 1 names 8-bit KV quantisation
+ * as the usual way to shrink the cache, the paper prescribes no scheme). Rows
+ * are coded when they are written, by yoco_global_kv_write and
+ * yoco_kv_cache_append, one fp32 scale per row and KV head, all in float32:
+ *   a = max|x| over the row's d numbers,  scale = a / 127,
+ *   code_e = round-half-even(x_e * (127 / a)), in [-127, 127]
+ * (a zero row: scale 0, codes 0), and the row stands for code_e * scale.
+ * Every element is off by at most scale / 2 = max|x| / 254. Attention reads the
+ * codes: yoco_cross_attn_decode, and yoco_cross_attn_prefill for up to 8 rows
+ * with the decode workspace (the exit row of an early-exit prefill); q and o
+ * are bf16, |q| below 65504 (the products run on fp16 operands, exactly for
+ * the codes and for bf16 queries of ordinary size). head_dim must be 128 and
+ * Hq / Hkv at most 4. A rolling window cache cannot be 8-bit.
+ * Layout of a plane per (sequence, KV head): blocks of 64 rows, each 64 x 128
+ * bytes (byte = code + 128) followed by the 64 fp32 scales of its rows, the
+ * scale of block row r at index (r % 8) * 8 + r / 8; 8448 bytes per block,
+ * ceil(N_cap / 64) blocks: 132 bytes per cached token and KV head and plane
+ * instead of 256 in bf16.
+ */
+
+/* Bytes the cache needs: 2 * B * Hkv * N_cap * d * sizeof(dtype); for
+ * YOCO_INT8 2 * B * Hkv * ceil(N_cap / 64) * 8448. Host only. */
 int yoco_kv_cache_bytes(int B, int Hkv, int d, int64_t N_cap, int dtype, size_t* bytes);
 
 /* Fill `out` for a caller-allocated block `mem` of `bytes` bytes (device
@@ -105,7 +131,8 @@ int yoco_swa_prefill(const void* q, const void* k, const void* v, void* o, int B
  * Store n projected rows K^[pos0..pos0+n), V^[pos0..pos0+n) of sequence b into
  * the cache (Eq. 2 is computed by the caller: RMSNorm and the two GEMMs).
  * k, v: [n,Hkv,d] of `src_dtype`; rows are converted to the cache dtype
- * (round to nearest even). Requires 0 <= pos0, pos0 + n <= N_cap, 0 <= b < B.
+ * (round to nearest even; coded as above for an 8-bit cache). Requires
+ * 0 <= pos0, pos0 + n <= N_cap, 0 <= b < B.
  * n == 0 is a no-op.
  */
 int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, int b, int64_t pos0,
@@ -114,7 +141,8 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
 /*
  * Cross-decoder attention of Eq. 3 for Tq query rows of sequence b; row i has
  * absolute position q_pos0 + i and attends to cache rows j <= q_pos0 + i
- * (causal). q, o: [Tq,Hq,d] of the cache dtype. Requires q_pos0 + Tq <= N_cap;
+ * (causal). q, o: [Tq,Hq,d] of the cache dtype (bf16 for an 8-bit cache).
+ * Requires q_pos0 + Tq <= N_cap;
  * the rows read must have been written.
  * workspace: optional device scratch (NULL = none), 16-byte aligned. With at
  * least yoco_cross_attn_decode_workspace(c, Hq) bytes, a call with Tq <= 8 rows
@@ -133,7 +161,8 @@ int yoco_cross_attn_decode_workspace(const yoco_kv_cache* c, int Hq, size_t* byt
 
 /*
  * One decode step of a cross-decoder layer (Fig. 3 "Generation"): for every
- * sequence b one query token; q, o: [B,Hq,d] of the cache dtype. lens: device
+ * sequence b one query token; q, o: [B,Hq,d] of the cache dtype (bf16 for an
+ * 8-bit cache). lens: device
  * int64 [B]; sequence b attends to cache rows [0, lens[b]) -- its own row has
  * been written before the call (Eq. 2 precedes Eq. 3, the mask is j <= i).
  * lens[b] is clamped to [0, N_cap]; a sequence with lens[b] == 0 gets zeros.

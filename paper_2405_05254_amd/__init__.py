@@ -5,7 +5,7 @@ the current HIP stream); every step of the path runs in the HIP kernels of
 libyoco.so. There is no CPU fallback: a missing library raises.
 """
 from .binding import (  # noqa: F401
-    F32, BF16, YocoError, KVCache, lib, lib_path,
+    F32, BF16, INT8, YocoError, KVCache, lib, lib_path,
     kv_cache_bytes, swa_prefill, global_kv_write, cross_attn_prefill,
     cross_attn_decode, cross_attn_decode_workspace, version,
     swa_cache_write, kv_cache_append, swa_decode,

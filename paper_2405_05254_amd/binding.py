@@ -4,7 +4,7 @@ import os
 
 import torch
 
-F32, BF16 = 0, 1
+F32, BF16, INT8 = 0, 1, 2
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
@@ -100,20 +100,32 @@ class KVCache:
     torch owns the memory, the descriptor is yoco_kv_cache."""
 
     def __init__(self, B, Hkv, d, N_cap, dtype=torch.bfloat16, device="cuda"):
-        if dtype not in (torch.float32, torch.bfloat16):
+        if dtype not in (torch.float32, torch.bfloat16, torch.int8):
             raise YocoError("unsupported cache dtype %s" % dtype)
-        code = F32 if dtype == torch.float32 else BF16
+        code = {torch.float32: F32, torch.bfloat16: BF16, torch.int8: INT8}[dtype]
         self.bytes = kv_cache_bytes(B, Hkv, d, N_cap, code)
         self.mem = torch.empty(self.bytes, dtype=torch.uint8, device=device)
         self.desc = _Cache()
         _check(lib().yoco_kv_cache_init(self.mem.data_ptr(), self.bytes, B, Hkv, d, N_cap, code, C.byref(self.desc)))
         self.B, self.Hkv, self.d, self.N_cap, self.dtype = B, Hkv, d, N_cap, dtype
+        self.io_dtype = torch.bfloat16 if dtype == torch.int8 else dtype     # of the queries and outputs on this cache
 
     def planes(self):
         """Views [B,Hkv,N_cap,d] of the K and V planes (for tests and for filling synthetic caches)."""
+        if self.dtype == torch.int8:
+            raise YocoError("an 8-bit cache is a run of blocks, not a [B,Hkv,N_cap,d] array: use blocks()")
         half = self.bytes // 2
         shape = (self.B, self.Hkv, self.N_cap, self.d)
         return (self.mem[:half].view(self.dtype).view(shape), self.mem[half:].view(self.dtype).view(shape))
+
+    def blocks(self):
+        """Byte views [B,Hkv,ceil(N_cap/64),8448] of the K and V planes of an 8-bit cache: per block 64 x 128 code
+        bytes (code + 128), then 64 float32 scales, the scale of block row r at index (r % 8) * 8 + r // 8."""
+        if self.dtype != torch.int8:
+            raise YocoError("blocks() is the layout of an 8-bit cache")
+        half = self.bytes // 2
+        shape = (self.B, self.Hkv, (self.N_cap + 63) // 64, 8448)
+        return self.mem[:half].view(shape), self.mem[half:].view(shape)
 
 
 def swa_prefill(q, k, v, window, scale, out=None):
@@ -141,7 +153,7 @@ def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None, workspace=None):
     """q [Tq,Hq,d] -> o [Tq,Hq,d], causal over the cache of sequence b (yoco_cross_attn_prefill).
     workspace: optional device scratch tensor (see cross_attn_decode_workspace) for few-row calls."""
     Tq, Hq, d = q.shape
-    if d != cache.d or q.dtype != cache.dtype:
+    if d != cache.d or q.dtype != cache.io_dtype:
         raise YocoError("q does not match the cache")
     o = torch.empty_like(q) if out is None else out
     ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
@@ -160,7 +172,7 @@ def cross_attn_decode_workspace(cache, Hq):
 def cross_attn_decode(cache, q, lens, scale, workspace, out=None):
     """q [B,Hq,d], lens int64 [B] (device) -> o [B,Hq,d] (yoco_cross_attn_decode)."""
     B, Hq, d = q.shape
-    if B != cache.B or d != cache.d or q.dtype != cache.dtype:
+    if B != cache.B or d != cache.d or q.dtype != cache.io_dtype:
         raise YocoError("q does not match the cache")
     if lens.dtype != torch.int64 or lens.shape != (B,):
         raise YocoError("lens must be int64 [B]")

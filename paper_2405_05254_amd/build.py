@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libyoco.so")
-SOURCES = ["yoco_api.hip", "attn_generic.hip", "swa_mfma.hip", "decode_bf16.hip", "gret_generic.hip", "gret_chunk.hip", "ceilings.hip"]
+SOURCES = ["yoco_api.hip", "attn_generic.hip", "swa_mfma.hip", "decode_bf16.hip", "gret_generic.hip", "gret_chunk.hip", "cache_i8.hip", "ceilings.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
          "-fno-honor-nans",        # fmax without NaN canonicalisation; -inf (the mask value) is still honoured

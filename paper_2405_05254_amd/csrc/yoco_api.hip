@@ -24,14 +24,23 @@ int hip_result(hipError_t e, const char* what) {
 
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 size_t elem_bytes(int dtype) { return dtype == YOCO_F32 ? 4 : 2; }
-bool dtype_ok(int dtype) { return dtype == YOCO_F32 || dtype == YOCO_BF16; }
+bool dtype_ok(int dtype) { return dtype == YOCO_F32 || dtype == YOCO_BF16; }                 // tensors
+bool cache_dtype_ok(int dtype) { return dtype_ok(dtype) || dtype == YOCO_INT8; }             // cache planes
+int io_dtype(const yoco_kv_cache& c) { return c.dtype == YOCO_INT8 ? YOCO_BF16 : c.dtype; }  // of q and o on this cache
+// Bytes of one sequence's share of a plane (all its KV heads).
+size_t plane_bytes_per_seq(const yoco_kv_cache& c) {
+  if (c.dtype == YOCO_INT8) return (size_t)c.Hkv * yoco::i8_plane_bytes(c.N_cap);
+  return (size_t)c.Hkv * c.N_cap * c.d * elem_bytes(c.dtype);
+}
 
 int check_cache(const yoco_kv_cache* c) {
   if (!c) return fail(YOCO_ERR_INVALID_ARG, "cache descriptor is null");
   if (!c->k || !c->v) return fail(YOCO_ERR_INVALID_ARG, "cache planes are null");
   if (c->B <= 0 || c->Hkv <= 0 || c->N_cap <= 0) return fail(YOCO_ERR_INVALID_ARG, "cache has a non-positive size");
-  if (!dtype_ok(c->dtype)) return fail(YOCO_ERR_UNSUPPORTED, "cache dtype %d", c->dtype);
+  if (!cache_dtype_ok(c->dtype)) return fail(YOCO_ERR_UNSUPPORTED, "cache dtype %d", c->dtype);
   if (c->d <= 0 || c->d > 256) return fail(YOCO_ERR_UNSUPPORTED, "head_dim %d not in [8, 256]", c->d);
+  if (c->dtype == YOCO_INT8 && !yoco::cache_i8_supported(c->d))
+    return fail(YOCO_ERR_UNSUPPORTED, "an 8-bit cache needs head_dim 128, not %d", c->d);
   if (c->d % 8) return fail(YOCO_ERR_ALIGNMENT, "head_dim %d is not a multiple of 8", c->d);
   if (!aligned16(c->k) || !aligned16(c->v)) return fail(YOCO_ERR_ALIGNMENT, "cache planes are not 16-byte aligned");
   return YOCO_OK;
@@ -79,7 +88,13 @@ int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* le
                float* ws, int splits, hipStream_t s, const char* what, const void* k_new = nullptr, const void* v_new = nullptr,
                int ring = 0) {
   hipError_t e;
-  if (yoco::decode_bf16_supported(c, Hq)) {
+  if (c.dtype == YOCO_INT8) {
+    if (!yoco::decode_i8_supported(c, Hq))
+      return fail(YOCO_ERR_UNSUPPORTED, "%s: an 8-bit cache serves up to 4 query heads per KV head, not %d", what, Hq / c.Hkv);
+    if (k_new) return fail(YOCO_ERR_UNSUPPORTED, "%s: no fused append into an 8-bit cache", what);
+    e = yoco::launch_decode_i8(c, q, lens, fixed_len, Hq, scale, ws, splits, o, s);
+    if (splits == 1) return hip_result(e, what);
+  } else if (yoco::decode_bf16_supported(c, Hq)) {
     e = yoco::launch_decode_bf16(c, q, lens, fixed_len, Hq, scale, ws, splits, o, k_new, v_new, ring, s);
     if (splits == 1) return hip_result(e, what);      // one split: pass 1 wrote the output
   } else {
@@ -90,7 +105,7 @@ int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* le
     e = yoco::launch_decode_generic(c, q, lens, fixed_len, Hq, scale, ws, splits, s);
   }
   if (e != hipSuccess) return hip_result(e, what);
-  return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, c.dtype, s), what);
+  return hip_result(yoco::launch_decode_merge(ws, o, c.B, Hq, c.d, splits, io_dtype(c), s), what);
 }
 
 int check_gret_shape(int B, int64_t T, int H, int dk, int dv, int dtype) {
@@ -116,9 +131,14 @@ const char* yoco_last_error_string(void) { return g_err; }
 int yoco_kv_cache_bytes(int B, int Hkv, int d, int64_t N_cap, int dtype, size_t* bytes) {
   if (!bytes) return fail(YOCO_ERR_INVALID_ARG, "bytes is null");
   if (B <= 0 || Hkv <= 0 || d <= 0 || N_cap <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive size");
-  if (!dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
+  if (!cache_dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
   if (d % 8) return fail(YOCO_ERR_ALIGNMENT, "head_dim %d is not a multiple of 8", d);
   if (d > 256) return fail(YOCO_ERR_UNSUPPORTED, "head_dim %d exceeds 256", d);
+  if (dtype == YOCO_INT8) {
+    if (!yoco::cache_i8_supported(d)) return fail(YOCO_ERR_UNSUPPORTED, "an 8-bit cache needs head_dim 128, not %d", d);
+    *bytes = (size_t)2 * B * Hkv * (size_t)yoco::i8_plane_bytes(N_cap);
+    return YOCO_OK;
+  }
   *bytes = (size_t)2 * B * Hkv * (size_t)N_cap * d * elem_bytes(dtype);
   return YOCO_OK;
 }
@@ -180,6 +200,10 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
   if (n == 0) return YOCO_OK;
   if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
+  if (c->dtype == YOCO_INT8) {
+    if (n * c->Hkv > (int64_t)1 << 32) return fail(YOCO_ERR_UNSUPPORTED, "too many rows for one call");
+    return hip_result(yoco::launch_kv_code_i8(*c, k, v, b, pos0, n, nullptr, src_dtype, (hipStream_t)stream), "global_kv_write");
+  }
   return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, 0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
 }
 
@@ -187,6 +211,7 @@ int yoco_swa_cache_write(const yoco_kv_cache* ring, const void* k, const void* v
                          int src_dtype, void* stream) {
   int rc = check_cache(ring);
   if (rc) return rc;
+  if (ring->dtype == YOCO_INT8) return fail(YOCO_ERR_UNSUPPORTED, "a rolling window cache cannot be 8-bit");
   if (n < 0) return fail(YOCO_ERR_INVALID_ARG, "negative row count");
   if (b < 0 || b >= ring->B) return fail(YOCO_ERR_INVALID_ARG, "sequence %d outside [0, %d)", b, ring->B);
   if (pos0 < 0) return fail(YOCO_ERR_INVALID_ARG, "negative position %lld", (long long)pos0);
@@ -207,6 +232,10 @@ int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, c
   if (!k || !v || !pos) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
   if (((uintptr_t)pos) & 7u) return fail(YOCO_ERR_ALIGNMENT, "pos is not 8-byte aligned");
+  if (c->dtype == YOCO_INT8) {
+    if (ring) return fail(YOCO_ERR_UNSUPPORTED, "a rolling window cache cannot be 8-bit");
+    return hip_result(yoco::launch_kv_code_i8(*c, k, v, 0, 0, c->B, pos, src_dtype, (hipStream_t)stream), "kv_cache_append");
+  }
   return hip_result(yoco::launch_kv_append(*c, k, v, pos, 0, ring, src_dtype, (hipStream_t)stream), "kv_cache_append");
 }
 
@@ -223,16 +252,16 @@ int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int 
   if (q_pos0 + Tq > c->N_cap)
     return fail(YOCO_ERR_INVALID_ARG, "query positions up to %lld exceed the cache capacity %lld",
                 (long long)(q_pos0 + Tq), (long long)c->N_cap);
-  const size_t eb = elem_bytes(c->dtype);
-  const int64_t plane_b = (int64_t)c->Hkv * c->N_cap * c->d;
+  const size_t eb = elem_bytes(io_dtype(*c));
+  const size_t seq_bytes = plane_bytes_per_seq(*c);
   if (workspace && !aligned16(workspace)) return fail(YOCO_ERR_ALIGNMENT, "workspace not 16-byte aligned");
   if (workspace && Tq <= kFewRows) {
     // A few rows cannot fill the chip one workgroup per query tile: treat each
     // row as a decode step of a one-sequence cache, split over the rows it sees.
     yoco_kv_cache one = *c;
     one.B = 1;
-    one.k = (char*)c->k + (size_t)b * plane_b * eb;
-    one.v = (char*)c->v + (size_t)b * plane_b * eb;
+    one.k = (char*)c->k + (size_t)b * seq_bytes;
+    one.v = (char*)c->v + (size_t)b * seq_bytes;
     const int splits = decode_splits(&one);
     const size_t need = (size_t)Hq * splits * yoco::partial_stride(c->d) * sizeof(float);
     if (workspace_bytes >= need) {
@@ -244,10 +273,13 @@ int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int 
       return YOCO_OK;
     }
   }
+  if (c->dtype == YOCO_INT8)
+    return fail(YOCO_ERR_UNSUPPORTED, "cross_attn_prefill over an 8-bit cache serves up to %d rows and needs the decode workspace",
+                (int)kFewRows);
   yoco::AttnView a;
   a.q = q; a.o = o;
-  a.k = (const char*)c->k + (size_t)b * plane_b * eb;
-  a.v = (const char*)c->v + (size_t)b * plane_b * eb;
+  a.k = (const char*)c->k + (size_t)b * seq_bytes;
+  a.v = (const char*)c->v + (size_t)b * seq_bytes;
   a.q_stride_t = (int64_t)Hq * c->d;
   a.q_stride_b = 0;
   a.kv_stride_n = c->d;
@@ -297,6 +329,7 @@ int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, const void* k_new,
   // ring, with lens clamped to its capacity (the kernels do), is Eq. 8.
   int rc = check_cache(ring);
   if (rc) return rc;
+  if (ring->dtype == YOCO_INT8) return fail(YOCO_ERR_UNSUPPORTED, "a rolling window cache cannot be 8-bit");
   rc = check_heads(Hq, ring->Hkv);
   if (rc) return rc;
   if (!q || !o || !lens || !workspace) return fail(YOCO_ERR_INVALID_ARG, "null pointer");

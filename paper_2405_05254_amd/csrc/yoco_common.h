@@ -91,6 +91,21 @@ hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64
                               float* ws, int splits, void* o_direct, const void* k_new, const void* v_new, int ring,
                               hipStream_t s);
 
+// 8-bit global cache (cache_i8.hip), head_dim 128: a plane per (sequence, KV head) is a run of 64-row blocks, each
+// 64 x 128 code bytes followed by the rows' 64 fp32 scales.
+constexpr int kI8BlockRows = 64;
+constexpr int kI8ScaleOffset = 64 * 128;                 // bytes from the start of a block to its scales
+constexpr int kI8BlockBytes = kI8ScaleOffset + 64 * 4;   // 8448 = 33 * 256
+__host__ __device__ inline int64_t i8_plane_bytes(int64_t N_cap) { return ((N_cap + 63) / 64) * kI8BlockBytes; }
+__host__ __device__ inline int i8_scale_index(int rho) { return (rho & 7) * 8 + (rho >> 3); }   // of block row rho
+bool cache_i8_supported(int d);
+bool decode_i8_supported(const yoco_kv_cache& c, int Hq);
+// pos == null: rows [n,Hkv,128] of sequence b to slots pos0 ..; pos != null: one row per sequence to slot pos[b].
+hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+                             const int64_t* pos, int src_dtype, hipStream_t s);
+hipError_t launch_decode_i8(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
+                            float* ws, int splits, void* o_direct, hipStream_t s);   // q, o bf16
+
 // Measured-ceiling microbenchmarks (ceilings.hip).
 hipError_t launch_mfma_ceiling(const void* seed, void* sink, int iters, int workgroups, hipStream_t s);
 hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s);

@@ -185,3 +185,39 @@ def test_gated_retention_calls_validate_before_launching():
     assert decode(dv=4) == -3
     assert decode(dt=-1) == -2
     assert decode(dk=136, dt=yoco.F32) == -2
+
+
+def test_eight_bit_cache_sizes_and_validation():
+    """The 8-bit global cache: 64-row blocks of 8448 bytes, head_dim 128 only, no rolling use; host-side checks."""
+    L = yoco.lib()
+    p = 0x7f0000000000
+    assert yoco.kv_cache_bytes(1, 1, 128, 64, yoco.INT8) == 2 * 8448
+    assert yoco.kv_cache_bytes(1, 1, 128, 65, yoco.INT8) == 2 * 2 * 8448          # a started block is a whole block
+    assert yoco.kv_cache_bytes(16, 8, 128, 32768, yoco.INT8) == 2 * 16 * 8 * 512 * 8448
+    # 132 bytes per token, head and plane: 0.516 of the bf16 cache
+    assert yoco.kv_cache_bytes(1, 8, 128, 524288, yoco.INT8) / yoco.kv_cache_bytes(1, 8, 128, 524288, yoco.BF16) == 132 / 256
+    n = C.c_size_t()
+    assert L.yoco_kv_cache_bytes(1, 8, 64, 100, yoco.INT8, C.byref(n)) == -2             # head_dim 128 only
+    d = yb._Cache()
+    need = yoco.kv_cache_bytes(2, 2, 128, 100, yoco.INT8)
+    assert L.yoco_kv_cache_init(p, need, 2, 2, 128, 100, yoco.INT8, C.byref(d)) == 0
+    assert d.k == p and d.v == p + need // 2 and d.dtype == yoco.INT8
+    assert L.yoco_kv_cache_init(p, need - 1, 2, 2, 128, 100, yoco.INT8, C.byref(d)) == -4
+    # writes and appends take f32 or bf16 rows; the usual range checks apply
+    assert L.yoco_global_kv_write(C.byref(d), p, p, 0, 99, 2, 1, None) == -1
+    assert L.yoco_global_kv_write(C.byref(d), p, p, 0, 0, 1, yoco.INT8, None) == -2       # rows are never given as codes
+    assert L.yoco_global_kv_write(C.byref(d), None, None, 0, 5, 0, 1, None) == 0
+    assert L.yoco_kv_cache_append(C.byref(d), p, p, p, 1, 1, None) == -2                  # no 8-bit ring
+    assert b"rolling" in L.yoco_last_error_string()
+    assert L.yoco_swa_cache_write(C.byref(d), p, p, 0, 0, 1, 1, None) == -2
+    ws, s = C.c_size_t(), C.c_int()
+    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 4, C.byref(ws), C.byref(s)) == 0
+    assert L.yoco_swa_decode(C.byref(d), p, None, None, p, p, 4, 1.0, p, ws.value, None) == -2
+    # many-row prefill over the codes has no kernel; without a workspace the few-row form cannot run either
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 50, 4, 1.0, None, 0, None) == -2
+    assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 2, 4, 1.0, None, 0, None) == -2
+    assert b"8-bit" in L.yoco_last_error_string()
+    # more than 4 query heads per KV head: refused before any launch
+    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 10, C.byref(ws), C.byref(s)) == 0
+    assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 10, 1.0, p, ws.value, None) == -2
+    assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 4, 1.0, p, 16, None) == -4
