@@ -97,14 +97,19 @@ typedef struct yoco_kv_cache {
  * Every element is off by at most scale / 2 = max|x| / 254. Attention reads the
  * codes: yoco_cross_attn_decode, and yoco_cross_attn_prefill for up to 8 rows
  * with the decode workspace (the exit row of an early-exit prefill); q and o
- * are bf16, |q| below 65504 (the products run on fp16 operands, exactly for
- * the codes and for bf16 queries of ordinary size). head_dim must be 128 and
+ * are bf16. head_dim must be 128 and
  * Hq / Hkv at most 4. A rolling window cache cannot be 8-bit.
- * Layout of a plane per (sequence, KV head): blocks of 64 rows, each 64 x 128
- * bytes (byte = code + 128) followed by the 64 fp32 scales of its rows, the
- * scale of block row r at index (r % 8) * 8 + r / 8; 8448 bytes per block,
- * ceil(N_cap / 64) blocks: 132 bytes per cached token and KV head and plane
- * instead of 256 in bf16.
+ * Layout of a plane per (sequence, KV head): ceil(N_cap / 64) blocks of 64 rows,
+ * 8448 bytes each: 8192 code bytes, then the rows' 64 fp32 scales in row order;
+ * 132 bytes per cached token, KV head and plane instead of 256 in bf16. The
+ * code bytes are ordered as the matrix cores take them. Row r (0..63) of a
+ * block, dim e (0..127):
+ *   K plane, code as a signed byte, at offset
+ *     ((((r/4)%4)*2 + e/64)*64 + ((e%64)/16)*16 + 4*(r/16) + r%4)*16 + e%16
+ *   V plane, byte = code + 128, stored transposed, at offset
+ *     ((e/16)*64 + (r/16)*16 + e%16)*16 + r%16
+ * Decode keeps 16 bits of each query below the largest |q| of its head (two
+ * int8 parts) and rounds each softmax weight times row scale to fp16.
  */
 
 /* Bytes the cache needs: 2 * B * Hkv * N_cap * d * sizeof(dtype); for

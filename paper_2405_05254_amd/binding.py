@@ -119,8 +119,8 @@ class KVCache:
         return (self.mem[:half].view(self.dtype).view(shape), self.mem[half:].view(self.dtype).view(shape))
 
     def blocks(self):
-        """Byte views [B,Hkv,ceil(N_cap/64),8448] of the K and V planes of an 8-bit cache: per block 64 x 128 code
-        bytes (code + 128), then 64 float32 scales, the scale of block row r at index (r % 8) * 8 + r // 8."""
+        """Byte views [B,Hkv,ceil(N_cap/64),8448] of the K and V planes of an 8-bit cache: per block 8192 code bytes
+        in the order yoco.h documents, then the 64 float32 scales of the block's rows."""
         if self.dtype != torch.int8:
             raise YocoError("blocks() is the layout of an 8-bit cache")
         half = self.bytes // 2

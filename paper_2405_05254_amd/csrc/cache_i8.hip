@@ -3,13 +3,17 @@
 // fp32 scale per row and KV head): the kernels that code rows into it and the
 // split-KV decode pass that reads it. head_dim 128.
 //
-// Memory layout of a plane (one per sequence and KV head): blocks of 64 rows;
-// a block is 64 x 128 code bytes (byte = code + 128, code in [-127, 127])
-// followed by the 64 fp32 scales of its rows, 8448 bytes = 33 x 256 in all, so a
-// wavefront streams a block with eight 1 KiB loads plus one 256-byte line and
-// never leaves contiguous memory. The scale of block row rho sits at index
-// (rho % 8) * 8 + rho / 8: the 8 lanes that share rows rho = r, r + 8, ... of a
-// step find their 8 scales in one 32-byte piece.
+// Memory layout of a plane (one per sequence and KV head): blocks of 64 rows,
+// 8448 bytes = 33 x 256 each: 8192 code bytes, then the 64 fp32 scales of the
+// rows in row order. The code bytes are ordered so that each of the eight 1 KiB
+// loads a wavefront issues per block (lane l reads bytes 16 l .. 16 l + 15) is
+// a ready matrix-core operand:
+//   K plane, code as a signed byte; row r, dim e sits at
+//     ((((r / 4) % 4) * 2 + e / 64) * 64 + ((e % 64) / 16) * 16 + 4 * (r / 16) + r % 4) * 16 + e % 16
+//     (load tau * 2 + half holds, for lane (n, qg), 16 dims of row 16 (n / 4) + 4 tau + n % 4);
+//   V plane, byte = code + 128, transposed; row r, dim e sits at
+//     ((e / 16) * 64 + (r / 16) * 16 + e % 16) * 16 + r % 16
+//     (load t holds, for lane (n, qg), the 16 rows 16 qg .. of dim 16 t + n).
 //
 // Coding rule (float32 throughout, because a rounding decides the integer):
 // a = max|x| over the row, scale = a / 127, code = rint(x * (127 / a)) clamped
@@ -28,6 +32,8 @@ constexpr float kNegBig = -1.0e30f;
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------- coding rows into the cache
 // One wavefront per (row, KV head, K or V): lane l holds elements 2l and 2l + 1.
@@ -58,120 +64,129 @@ __global__ void __launch_bounds__(256) kv_code_i8_kernel(yoco_kv_cache c, const 
   const float scale = a > 0.f ? a / 127.f : 0.f;
   const float y0 = fminf(fmaxf(rintf(x0 * inv), -127.f), 127.f);
   const float y1 = fminf(fmaxf(rintf(x1 * inv), -127.f), 127.f);
-  const unsigned w = (unsigned)((int)y0 + 128) | ((unsigned)((int)y1 + 128) << 8);
   char* blk = (char*)(which ? c.v : c.k) + ((int64_t)b * c.Hkv + g) * i8_plane_bytes(c.N_cap) + (slot >> 6) * kI8BlockBytes;
   const int rho = (int)(slot & 63);
-  *(unsigned short*)(blk + rho * kD + lane * 2) = (unsigned short)w;
-  if (lane == 0) *(float*)(blk + kI8ScaleOffset + 4 * i8_scale_index(rho)) = scale;
+  if (which) {            // transposed plane: the row's bytes lie 16 apart
+    blk[i8_v_offset(rho, lane * 2)] = (char)((int)y0 + 128);
+    blk[i8_v_offset(rho, lane * 2 + 1)] = (char)((int)y1 + 128);
+  } else {                // two neighbouring dims share a 16-byte piece
+    *(unsigned short*)(blk + i8_k_offset(rho, lane * 2)) = (unsigned short)(((unsigned)(int)y0 & 0xffu) | (((unsigned)(int)y1 & 0xffu) << 8));
+  }
+  if (lane == 0) *(float*)(blk + kI8ScaleOffset + 4 * rho) = scale;
 }
 
 // ---------------------------------------------------------------- decode pass 1 over the coded cache
+// Both contractions run on the matrix cores, whose operands are exactly what the block layout delivers:
+//   scores  S^T[row][head] = K[row][dim] . q[head][dim]      v_mfma_i32_16x16x64_i8, K codes as loaded (no conversion);
+//           q is split into two int8 parts per head, q = s1 * hi + (s1 / 254) * lo, which keeps 16 bits below max|q|
+//   output  O^T[dim][head] += V^T[dim][row] . w[row][head]   v_mfma_f32_16x16x32_f16, V codes turned into exact fp16
+//           integers (2 VALU ops per 4 codes), w = softmax weight * row scale in fp16, kept <= 1 by running its own maximum
+// Lane (n = lane % 16, qg = lane / 16) owns head n (lanes n >= G idle along) and rows 16 qg .. 16 qg + 15 of a block.
 __device__ __forceinline__ f16x2 as_f16x2(unsigned x) { return __builtin_bit_cast(f16x2, x); }
 
-// Two code bytes -> two exact fp16 integers: the byte under exponent bits 0x64 is 1024 + byte, then - (1024 + 128).
+// Two code bytes (code + 128) -> two exact fp16 integers: a byte under exponent bits 0x64 is 1024 + byte, then - (1024 + 128).
 template <unsigned SEL>
-__device__ __forceinline__ f16x2 codes_f16(unsigned w) {
+__device__ __forceinline__ unsigned codes_f16(unsigned w) {
   const unsigned p = __builtin_amdgcn_perm(0x64646464u, w, SEL);
-  return as_f16x2(p) - (f16x2){(_Float16)1152.f, (_Float16)1152.f};
+  return __builtin_bit_cast(unsigned, as_f16x2(p) - (f16x2){(_Float16)1152.f, (_Float16)1152.f});
 }
-__device__ __forceinline__ void row_codes_f16(const u32x4& w, f16x2 (&out)[8]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    out[2 * i] = codes_f16<0x04010400u>(w[i]);       // bytes 0, 1
-    out[2 * i + 1] = codes_f16<0x04030402u>(w[i]);   // bytes 2, 3
-  }
+// 8 code bytes (two dwords) -> the 8 fp16 of one MFMA operand
+__device__ __forceinline__ f16x8 codes8_f16(unsigned w0, unsigned w1) {
+  const u32x4 r = {codes_f16<0x04010400u>(w0), codes_f16<0x04030402u>(w0), codes_f16<0x04010400u>(w1), codes_f16<0x04030402u>(w1)};
+  return __builtin_bit_cast(f16x8, r);
 }
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-__device__ __forceinline__ float row8_sum(float x) {   // sum over 8 consecutive lanes, every lane gets the total
-  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);   // row_half_mirror: quads 0<->1, 2<->3
-  return x;
+__device__ __forceinline__ unsigned pack_f16(float a, float b) {      // round to nearest even
+  return __builtin_bit_cast(unsigned, (f16x2){(_Float16)a, (_Float16)b});
 }
 
-constexpr int R = 8;       // rows per lane and step; 8 lanes share a row, so a step is one 64-row block
+struct Block {             // what a lane holds of one 64-row block
+  u32x4 k[8];              // [tau * 2 + half]: K codes of row 16 (n / 4) + 4 tau + n % 4, dims 64 half + 16 qg ..
+  u32x4 v[8];              // [t]: V codes of dim 16 t + n, rows 16 qg .. 16 qg + 15
+  float ks, vs;            // scales of row `lane`: one coalesced 256-byte load per plane
+};
 
 template <int G>
 struct State {
-  float m[G], l[G], o[G][16];
-};
-
-struct Block {             // what a lane holds of one block: 16 code bytes of 8 rows of K and V, and those rows' scales
-  u32x4 k[R], v[R];
-  f32x4 ks[2], vs[2];
+  float m, l, mo;          // running max of the scores, partial sum of weights, running max of score + log2(row scale of V)
+  f32x4 o[8];              // O^T[16 t + 4 qg + i][n], relative to 2^mo
 };
 
 template <int G, bool TAIL>
-__device__ __forceinline__ void step(State<G>& st, const f16x2 (&qh)[G][8], const Block& x, float scale_log2, int r, int nvalid) {
-  float s[R][G];
+__device__ __forceinline__ void step(State<G>& st, const i32x4 (&qhi)[2], const i32x4 (&qlo)[2], float qs, const Block& x, int qg,
+                                     int nvalid, float (*sc)[64]) {
+  // Lane (n, qg) needs the scales of rows 16 qg .. 16 qg + 15: pass them through the wavefront's own LDS lines
+  // (a wavefront's LDS operations complete in order, so no barrier is involved).
+  const int lane = threadIdx.x & 63;
+  sc[0][lane] = x.ks;
+  sc[1][lane] = x.vs;
+  f32x4 ks[4], vs[4];
 #pragma unroll
-  for (int u = 0; u < R; ++u) {
-    f16x2 kk[8];
-    row_codes_f16(x.k[u], kk);
-    const float f = x.ks[u >> 2][u & 3] * scale_log2;
+  for (int i = 0; i < 4; ++i) {
+    ks[i] = *(const f32x4*)&sc[0][qg * 16 + i * 4];
+    vs[i] = *(const f32x4*)&sc[1][qg * 16 + i * 4];
+  }
+  float s[16], t[16];
+  float smax = -INFINITY, tmax = -INFINITY;
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float a = 0.f;
+  for (int tau = 0; tau < 4; ++tau) {
+    i32x4 hi = {0, 0, 0, 0}, lo = {0, 0, 0, 0};
+    hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, x.k[tau * 2]), qhi[0], hi, 0, 0, 0);
+    hi = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, x.k[tau * 2 + 1]), qhi[1], hi, 0, 0, 0);
+    lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, x.k[tau * 2]), qlo[0], lo, 0, 0, 0);
+    lo = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, x.k[tau * 2 + 1]), qlo[1], lo, 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) a = __builtin_amdgcn_fdot2(qh[h][i], kk[i], a, false);
-      a = row8_sum(a) * f;
-      if (TAIL && (u * 8 + r >= nvalid)) a = -INFINITY;     // also discards whatever an unwritten scale holds
-      s[u][h] = a;
+    for (int i = 0; i < 4; ++i) {
+      const int r = tau * 4 + i;
+      float a = (float)(__mul24(hi[i], 254) + lo[i]) * (ks[tau][i] * qs);   // |hi| < 2^21
+      float b = a + __builtin_amdgcn_logf(vs[tau][i]);               // log2; a zero row of V gets -inf, weight 0
+      if (TAIL && (qg * 16 + r >= nvalid)) { a = -INFINITY; b = -INFINITY; }   // also discards what unwritten scales hold
+      s[r] = a;
+      t[r] = b;
+      smax = fmaxf(smax, a);
+      tmax = fmaxf(tmax, b);
     }
   }
-  float pv[R][G];
+  // the four lanes of a head share the maxima: their rows meet in the same accumulators
+  smax = fmaxf(smax, __shfl_xor(smax, 16));
+  smax = fmaxf(smax, __shfl_xor(smax, 32));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+  const float m_new = fmaxf(st.m, smax), mo_new = fmaxf(st.mo, tmax);
+  float psum = 0.f, w[16];
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float mx = s[0][h];
-#pragma unroll
-    for (int u = 1; u < R; ++u) mx = fmaxf(mx, s[u][h]);
-    const float m_new = fmaxf(st.m[h], mx);
-    const float alpha = __builtin_amdgcn_exp2f(st.m[h] - m_new);
-    float psum = 0.f;
-#pragma unroll
-    for (int u = 0; u < R; ++u) {
-      const float p = __builtin_amdgcn_exp2f(s[u][h] - m_new);
-      psum += p;
-      const float w = p * x.vs[u >> 2][u & 3];
-      pv[u][h] = (TAIL && (u * 8 + r >= nvalid)) ? 0.f : w;
-    }
-    st.l[h] = st.l[h] * alpha + psum;
-    st.m[h] = m_new;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) st.o[h][i] *= alpha;
+  for (int r = 0; r < 16; ++r) {
+    psum += __builtin_amdgcn_exp2f(s[r] - m_new);
+    w[r] = __builtin_amdgcn_exp2f(t[r] - mo_new);
   }
+  st.l = st.l * __builtin_amdgcn_exp2f(st.m - m_new) + psum;
+  st.m = m_new;
+  if (__builtin_amdgcn_ballot_w64(mo_new != st.mo)) {                  // rare once the stream has met its large scores
+    const float alpha = __builtin_amdgcn_exp2f(st.mo - mo_new);
 #pragma unroll
-  for (int u = 0; u < R; ++u) {
-    f16x2 vv[8];
-    row_codes_f16(x.v[u], vv);
+    for (int tt = 0; tt < 8; ++tt) st.o[tt] *= alpha;
+    st.mo = mo_new;
+  }
+  const u32x4 pa = {pack_f16(w[0], w[1]), pack_f16(w[2], w[3]), pack_f16(w[4], w[5]), pack_f16(w[6], w[7])};
+  const u32x4 pb = {pack_f16(w[8], w[9]), pack_f16(w[10], w[11]), pack_f16(w[12], w[13]), pack_f16(w[14], w[15])};
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        st.o[h][2 * i] = fmaf(pv[u][h], (float)vv[i][0], st.o[h][2 * i]);
-        st.o[h][2 * i + 1] = fmaf(pv[u][h], (float)vv[i][1], st.o[h][2 * i + 1]);
-      }
-    }
+  for (int tt = 0; tt < 8; ++tt) {
+    st.o[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(codes8_f16(x.v[tt][0], x.v[tt][1]), __builtin_bit_cast(f16x8, pa), st.o[tt], 0, 0, 0);
+    st.o[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(codes8_f16(x.v[tt][2], x.v[tt][3]), __builtin_bit_cast(f16x8, pb), st.o[tt], 0, 0, 0);
   }
 }
 
 // Workgroup = 4 wavefronts on one (sequence, KV head, split); each wavefront walks a contiguous run of blocks,
-// the next block's loads in flight while the current one is reduced. Every group of 8 lanes keeps its own online
-// softmax state for the G query heads; states meet once at the end, as in the bf16 kernel. q, o are bf16.
+// the next block's loads in flight while the current one is reduced. q, o are bf16.
 template <int G>
-__global__ void __launch_bounds__(256) decode_i8_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
+__global__ void __launch_bounds__(256, 2) decode_i8_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
                                                         const int64_t* __restrict__ lens, int64_t fixed_len, int Hq, float scale_log2,
                                                         float* __restrict__ ws, int splits, bf16_t* __restrict__ o_direct) {
   __shared__ float red_o[4][G][kD];
   __shared__ float red_ml[4][G][2];
+  __shared__ __attribute__((aligned(16))) float scales[4][2][64];
   const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r = lane >> 3, seg = lane & 7;
+  const int n = lane & 15, qg = lane >> 4;
 
   const int64_t len_raw = lens ? lens[b] : fixed_len;
   const int64_t len = len_raw < 0 ? 0 : (len_raw > c.N_cap ? c.N_cap : len_raw);
@@ -182,26 +197,59 @@ __global__ void __launch_bounds__(256) decode_i8_kernel(yoco_kv_cache c, const b
   const int64_t w_lo = j_lo + wave * sub;
   const int64_t w_hi = (w_lo + sub < j_hi) ? w_lo + sub : j_hi;
 
-  f16x2 qh[G][8];
+  // The query of head n as two int8 operands: dims 64 half + 16 qg + j in byte j of half `half`.
+  i32x4 qhi[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, qlo[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+  float qs = 0.f;
+  {
+    float x[32];
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    const bf16_t* qp = q + ((int64_t)b * Hq + g * G + h) * kD + seg * 16;
-    const u32x4 lo = *(const u32x4*)qp, hi = *(const u32x4*)(qp + 8);
+    for (int i = 0; i < 32; ++i) x[i] = 0.f;
+    if (n < G) {
+      const bf16_t* qp = q + ((int64_t)b * Hq + g * G + n) * kD + qg * 16;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const unsigned w = i < 4 ? lo[i] : hi[i - 4];
-      qh[h][i] = (f16x2){(_Float16)__uint_as_float(w << 16), (_Float16)__uint_as_float(w & 0xffff0000u)};
+      for (int half = 0; half < 2; ++half) {
+        const u32x4 a = *(const u32x4*)(qp + half * 64), bq = *(const u32x4*)(qp + half * 64 + 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const unsigned w = i < 4 ? a[i] : bq[i - 4];
+          x[half * 16 + 2 * i] = __uint_as_float(w << 16);
+          x[half * 16 + 2 * i + 1] = __uint_as_float(w & 0xffff0000u);
+        }
+      }
     }
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(x[i]));
+    amax = fmaxf(amax, __shfl_xor(amax, 16));
+    amax = fmaxf(amax, __shfl_xor(amax, 32));
+    const float s1 = amax / 127.f, s2 = amax / 32258.f;                          // 32258 = 127 * 254
+    const float inv1 = amax > 0.f ? 127.f / amax : 0.f, inv2 = amax > 0.f ? 32258.f / amax : 0.f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        unsigned ph = 0, pl = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float v = x[half * 16 + wd * 4 + j];
+          const float h = fminf(fmaxf(rintf(v * inv1), -127.f), 127.f);
+          const float lo = fminf(fmaxf(rintf(fmaf(-h, s1, v) * inv2), -127.f), 127.f);
+          ph |= ((unsigned)(int)h & 0xffu) << (8 * j);
+          pl |= ((unsigned)(int)lo & 0xffu) << (8 * j);
+        }
+        qhi[half][wd] = (int)ph;
+        qlo[half][wd] = (int)pl;
+      }
+    }
+    qs = s2 * scale_log2;
   }
 
   State<G> st;
+  st.m = kNegBig;
+  st.mo = kNegBig;
+  st.l = 0.f;
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    st.m[h] = kNegBig;
-    st.l[h] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) st.o[h][i] = 0.f;
-  }
+  for (int tt = 0; tt < 8; ++tt) st.o[tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const int64_t plane = ((int64_t)b * c.Hkv + g) * (i8_plane_bytes(c.N_cap) / 16);   // in 16-byte units
   const u32x4* kp = (const u32x4*)c.k + plane;
@@ -212,72 +260,55 @@ __global__ void __launch_bounds__(256) decode_i8_kernel(yoco_kv_cache c, const b
     auto load = [&](int64_t row0) {                       // row0 is a multiple of 64
       const int64_t base = (row0 >> 6) * (kI8BlockBytes / 16);
 #pragma unroll
-      for (int u = 0; u < R; ++u) {
+      for (int u = 0; u < 8; ++u) {
         nx.k[u] = __builtin_nontemporal_load(kp + base + u * 64 + lane);
         nx.v[u] = __builtin_nontemporal_load(vp + base + u * 64 + lane);
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        nx.ks[i] = __builtin_nontemporal_load((const f32x4*)(kp + base + kI8ScaleOffset / 16 + r * 2 + i));
-        nx.vs[i] = __builtin_nontemporal_load((const f32x4*)(vp + base + kI8ScaleOffset / 16 + r * 2 + i));
-      }
+      nx.ks = __builtin_nontemporal_load((const float*)(kp + base + kI8ScaleOffset / 16) + lane);
+      nx.vs = __builtin_nontemporal_load((const float*)(vp + base + kI8ScaleOffset / 16) + lane);
     };
     load(w_lo);
     int64_t row0 = w_lo;
     for (; row0 + 64 < w_hi; row0 += 64) {
       const Block cur = nx;
       load(row0 + 64);
-      step<G, false>(st, qh, cur, scale_log2, r, 64);
+      step<G, false>(st, qhi, qlo, qs, cur, qg, 64, scales[wave]);
     }
-    step<G, true>(st, qh, nx, scale_log2, r, (int)(w_hi - row0));   // last block of the run, 1..64 rows
+    step<G, true>(st, qhi, qlo, qs, nx, qg, (int)(w_hi - row0), scales[wave]);   // last block of the run, 1..64 rows
   }
 
-  // merge the 8 lane groups of the wave
+  // One state per head and wavefront: gather the partial sums of the four row groups, rebase the output on 2^m.
+  float l = st.l;
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  const float f = __builtin_amdgcn_exp2f(st.mo - st.m);   // the output's own maximum differs by the V scales: finite
+  if (n < G) {
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float M = st.m[h];
-    M = fmaxf(M, __shfl_xor(M, 8));
-    M = fmaxf(M, __shfl_xor(M, 16));
-    M = fmaxf(M, __shfl_xor(M, 32));
-    const float f = __builtin_amdgcn_exp2f(st.m[h] - M);
-    float l = st.l[h] * f;
-    l += __shfl_xor(l, 8);
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    for (int tt = 0; tt < 8; ++tt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float x = st.o[h][i] * f;
-      x += __shfl_xor(x, 8);
-      x += __shfl_xor(x, 16);
-      x += __shfl_xor(x, 32);
-      st.o[h][i] = x;
-    }
-    if (lane < 8) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) red_o[wave][h][seg * 16 + i] = st.o[h][i];
-      if (lane == 0) { red_ml[wave][h][0] = M; red_ml[wave][h][1] = l; }
-    }
+      for (int i = 0; i < 4; ++i) red_o[wave][n][tt * 16 + qg * 4 + i] = st.o[tt][i] * f;
+    if (qg == 0) { red_ml[wave][n][0] = st.m; red_ml[wave][n][1] = l; }
   }
   __syncthreads();
   for (int t = threadIdx.x; t < G * kD; t += 256) {
     const int h = t / kD, e = t % kD;
     const float M = fmaxf(fmaxf(red_ml[0][h][0], red_ml[1][h][0]), fmaxf(red_ml[2][h][0], red_ml[3][h][0]));
-    float l = 0.f, o = 0.f;
+    float ls = 0.f, o = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float f = __builtin_amdgcn_exp2f(red_ml[w][h][0] - M);
-      l = fmaf(f, red_ml[w][h][1], l);
-      o = fmaf(f, red_o[w][h][e], o);
+      const float fw = __builtin_amdgcn_exp2f(red_ml[w][h][0] - M);
+      ls = fmaf(fw, red_ml[w][h][1], ls);
+      o = fmaf(fw, red_o[w][h][e], o);
     }
     if (o_direct) {
-      o_direct[((size_t)b * Hq + g * G + h) * kD + e] = f32_to_bf16(l > 0.f ? o / l : 0.f);
+      o_direct[((size_t)b * Hq + g * G + h) * kD + e] = f32_to_bf16(ls > 0.f ? o / ls : 0.f);
       continue;
     }
     float* out = ws + (((size_t)b * Hq + g * G + h) * splits + sp) * partial_stride(kD);
     out[e] = o;
     if (e == 0) {
-      out[kD] = (l > 0.f) ? M * kLn2 : -INFINITY;
-      out[kD + 1] = l;
+      out[kD] = (ls > 0.f) ? M * kLn2 : -INFINITY;
+      out[kD + 1] = ls;
     }
   }
 }

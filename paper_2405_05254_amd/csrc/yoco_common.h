@@ -92,12 +92,17 @@ hipError_t launch_decode_bf16(const yoco_kv_cache& c, const void* q, const int64
                               hipStream_t s);
 
 // 8-bit global cache (cache_i8.hip), head_dim 128: a plane per (sequence, KV head) is a run of 64-row blocks, each
-// 64 x 128 code bytes followed by the rows' 64 fp32 scales.
+// 8192 code bytes followed by the rows' 64 fp32 scales in row order. Byte offsets of (block row rho, dim e) inside a block:
 constexpr int kI8BlockRows = 64;
 constexpr int kI8ScaleOffset = 64 * 128;                 // bytes from the start of a block to its scales
 constexpr int kI8BlockBytes = kI8ScaleOffset + 64 * 4;   // 8448 = 33 * 256
 __host__ __device__ inline int64_t i8_plane_bytes(int64_t N_cap) { return ((N_cap + 63) / 64) * kI8BlockBytes; }
-__host__ __device__ inline int i8_scale_index(int rho) { return (rho & 7) * 8 + (rho >> 3); }   // of block row rho
+__host__ __device__ inline int i8_k_offset(int rho, int e) {      // K plane: signed code bytes
+  return (((((rho >> 2) & 3) * 2 + (e >> 6)) * 64) + ((e >> 4) & 3) * 16 + 4 * (rho >> 4) + (rho & 3)) * 16 + (e & 15);
+}
+__host__ __device__ inline int i8_v_offset(int rho, int e) {      // V plane: bytes code + 128, transposed
+  return (((e >> 4) * 64) + (rho >> 4) * 16 + (e & 15)) * 16 + (rho & 15);
+}
 bool cache_i8_supported(int d);
 bool decode_i8_supported(const yoco_kv_cache& c, int Hq);
 // pos == null: rows [n,Hkv,128] of sequence b to slots pos0 ..; pos != null: one row per sequence to slot pos[b].

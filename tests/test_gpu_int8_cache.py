@@ -35,17 +35,20 @@ def host(t):
 
 
 def read_cache(cache):
-    """(codes int16 [B,Hkv,NB*64,128], scales float32 [B,Hkv,NB*64]) of both planes, decoded from the block layout:
-    64 x 128 bytes (code + 128), then 64 scales with block row r at index (r % 8) * 8 + r // 8."""
+    """(codes int16 [B,Hkv,NB*64,128], scales float32 [B,Hkv,NB*64]) of both planes, decoded from the documented block
+    layout: 8192 code bytes in matrix-operand order (K signed, V as code + 128 and transposed), then 64 scales in row order."""
+    r, e = np.meshgrid(np.arange(64), np.arange(D), indexing="ij")
+    k_off = ((((r // 4) % 4) * 2 + e // 64) * 64 + ((e % 64) // 16) * 16 + 4 * (r // 16) + r % 4) * 16 + e % 16
+    v_off = ((e // 16) * 64 + (r // 16) * 16 + e % 16) * 16 + r % 16
+    assert len(np.unique(k_off)) == 8192 and len(np.unique(v_off)) == 8192       # both are permutations of the block
     out = []
-    rho = np.arange(64)
-    where = (rho % 8) * 8 + rho // 8
-    for plane in cache.blocks():
+    for plane, off, signed in zip(cache.blocks(), (k_off, v_off), (True, False)):
         raw = plane.cpu().numpy()
         B, Hkv, NB, _ = raw.shape
-        codes = raw[..., :8192].reshape(B, Hkv, NB * 64, D).astype(np.int16) - 128
-        scales = np.ascontiguousarray(raw[..., 8192:]).view(np.float32).reshape(B, Hkv, NB, 64)[..., where].reshape(B, Hkv, NB * 64)
-        out.append((codes, scales))
+        by = raw[..., :8192][..., off]                                            # [B,Hkv,NB,64,128]
+        codes = by.view(np.int8).astype(np.int16) if signed else by.astype(np.int16) - 128
+        scales = np.ascontiguousarray(raw[..., 8192:]).view(np.float32).reshape(B, Hkv, NB * 64)
+        out.append((codes.reshape(B, Hkv, NB * 64, D), scales))
     return out
 
 
@@ -78,8 +81,9 @@ def test_global_kv_write_codes_are_exact(yoco, src, N_cap, pos0, n):
             rc, rs = oracle.kv_quantise_int8(x.astype(np.float32))          # [n,Hkv,128], [n,Hkv]
             assert np.array_equal(codes[1, :, pos0:pos0 + n], rc.transpose(1, 0, 2).astype(np.int16)), name
             assert np.array_equal(scales[1, :, pos0:pos0 + n].view(np.uint32), rs.T.copy().view(np.uint32)), name
-        # nothing else was written: sequence 0 and the rows around keep the fill pattern
-        assert np.all(codes[0] == 0xAB - 128) and np.all(codes[1, :, :pos0] == 0xAB - 128) and np.all(codes[1, :, pos0 + n:] == 0xAB - 128)
+        # nothing else was written: sequence 0 and the rows around keep the fill pattern (0xAB as a K byte or as a V byte)
+        fillc = 0xAB - 256 if name == "k" else 0xAB - 128
+        assert np.all(codes[0] == fillc) and np.all(codes[1, :, :pos0] == fillc) and np.all(codes[1, :, pos0 + n:] == fillc)
         fill = np.frombuffer(bytes([0xAB] * 4), dtype=np.float32)[0]
         keep = np.ones(scales.shape, bool)
         keep[1, :, pos0:pos0 + n] = False
@@ -97,15 +101,15 @@ def test_append_codes_rows_at_device_positions(yoco):
     yoco.kv_cache_append(cache, dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(pos).cuda(), False)
     torch.cuda.synchronize()
     (kc, ks), (vc, vs) = read_cache(cache)
-    for x, codes, scales in ((k, kc, ks), (v, vc, vs)):
+    for x, codes, scales, fillc in ((k, kc, ks, 0x11), (v, vc, vs, 0x11 - 128)):
         rc, rs = oracle.kv_quantise_int8(x.astype(np.float32))
         for b in range(3):
             assert np.array_equal(codes[b, :, pos[b]], rc[b].astype(np.int16))
             assert np.array_equal(scales[b, :, pos[b]].view(np.uint32), rs[b].view(np.uint32))
             other = np.ones(codes.shape[2], bool)
             other[pos[b]] = False
-            assert np.all(codes[b][:, other] == 0x11 - 128)
-        assert np.all(codes[3:] == 0x11 - 128)
+            assert np.all(codes[b][:, other] == fillc)
+        assert np.all(codes[3:] == fillc)
     with pytest.raises(yoco.YocoError):
         yoco.kv_cache_append(cache, dev(k, "bf16"), dev(v, "bf16"), torch.from_numpy(pos).cuda(), True)
 
