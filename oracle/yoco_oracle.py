@@ -142,7 +142,8 @@ def yoco_stack(tokens, w, mode="full"):
     'gret', W_gamma [dm,Hq] and W_gate [dm,Hq*d] with the temperature w['tau']:
     the self-decoder then uses gated retention, Eq. 7); 'kv' = {ln, W_K, W_V};
     'cross' = list of layers with keys ln1, W_Q, W_O, ln2, W_G, W_1, W_2;
-    'final_ln', 'W_out'; ints 'Hq', 'Hkv_self', 'Hkv', 'd', 'window'; 'eps'.
+    'final_ln', 'W_out'; ints 'Hq', 'Hkv_self', 'Hkv', 'd', 'window'; 'eps';
+    optional 'cache_bits' = 8: the global cache holds 8-bit codes (kv_quantise_int8).
     mode 'full': every row goes through the cross-decoder -> logits [T,vocab].
     mode 'early_exit' (Fig. 3, section 2.3): the self-decoder and Eq. 2 run on
     all rows, only the last row enters the cross-decoder -> logits [1,vocab].
@@ -163,6 +164,9 @@ def yoco_stack(tokens, w, mode="full"):
             Y = A @ np.asarray(L["W_O"], F64) + X
         X = swiglu(rmsnorm(Y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + Y
     Khat, Vhat = global_kv(X, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)  # Eq. 2
+    if w.get("cache_bits") == 8:                          # the cache stores 8-bit codes: attention sees what they stand for
+        Khat = kv_dequantise_int8(*kv_quantise_int8(Khat))
+        Vhat = kv_dequantise_int8(*kv_quantise_int8(Vhat))
     if mode == "early_exit":
         X, q_pos0 = X[T - 1:T], T - 1
     elif mode == "full":
@@ -242,6 +246,9 @@ def yoco_stack_generate(tokens, w):
             y = a @ np.asarray(L["W_O"], F64) + x
             x = swiglu(rmsnorm(y, L["ln2"], eps), L["W_G"], L["W_1"], L["W_2"]) + y
         kh, vh = global_kv(x, w["kv"]["ln"], w["kv"]["W_K"], w["kv"]["W_V"], w["Hkv"], eps)
+        if w.get("cache_bits") == 8:
+            kh = kv_dequantise_int8(*kv_quantise_int8(kh))
+            vh = kv_dequantise_int8(*kv_quantise_int8(vh))
         Khat.append(kh[0])
         Vhat.append(vh[0])
         Kc, Vc = np.stack(Khat), np.stack(Vhat)

@@ -36,8 +36,9 @@ class YocoStack:
     """weights: the dict produced by the synthetic generator (numpy arrays);
     dtype: torch.float32 or torch.bfloat16."""
 
-    def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32):
+    def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32, cache_dtype=None):
         self.dtype, self.device, self.glue = dtype, device, glue_dtype
+        self.cache_dtype = dtype if cache_dtype is None else cache_dtype   # torch.int8: the global cache holds 8-bit codes
         self.capture = None          # dict layer-name -> (q, k, v, o) when set by a test
 
         def dev(a):
@@ -101,7 +102,7 @@ class YocoStack:
         k = (xn @ self.kv["W_K"]).to(self.dtype).view(T, self.Hkv, self.d)
         v = (xn @ self.kv["W_V"]).to(self.dtype).view(T, self.Hkv, self.d)
         if cache is None:
-            cache = yb.KVCache(1, self.Hkv, self.d, T, self.dtype, self.device)
+            cache = yb.KVCache(1, self.Hkv, self.d, T, self.cache_dtype, self.device)
         yb.global_kv_write(cache, k, v, 0, pos0)
         return cache
 
@@ -169,7 +170,7 @@ class YocoStack:
             rings = [torch.zeros(1, self.Hq, self.d, self.d, dtype=torch.float32, device=self.device) for _ in self.self_layers]
         else:
             rings = [yb.KVCache(1, self.Hkv_self, self.d, self.window, self.dtype, self.device) for _ in self.self_layers]
-        cache = yb.KVCache(1, self.Hkv, self.d, max_len, self.dtype, self.device)
+        cache = yb.KVCache(1, self.Hkv, self.d, max_len, self.cache_dtype, self.device)
         ws = []
         for c in ((cache, cache) if self.self_kind == "gret" else (rings[0], cache)):
             nbytes, _ = yb.cross_attn_decode_workspace(c, self.Hq)

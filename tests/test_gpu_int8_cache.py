@@ -237,3 +237,35 @@ def test_full_size_decode_over_codes_sampled(yoco):
         print("int8 full-size decode (b %d, g %d), %d splits: max_abs %.3e mean_rel %.3e" % (b, g, splits, st["max_abs"], st["mean_rel"]),
               flush=True)
         assert st["max_abs"] <= ys.TOL["bf16"]["max_abs"] and st["mean_rel"] <= ys.TOL["bf16"]["mean_rel"], st
+
+
+# ------------------------------------------------------------ the stack over an 8-bit global cache
+def test_stack_with_coded_cache_prefill_and_generation(yoco):
+    """A small bf16 stack (head_dim 128, window 64) whose global cache holds 8-bit codes: early-exit prefill of 150
+    tokens, then 30 decode steps, against the fp64 oracle stack that codes its K^, V^ rows the same way; and the
+    distance to the stack with an uncoded cache, which the codes may move only a little."""
+    from paper_2405_05254_amd.stack import YocoStack
+    s = dict(d_model=256, Hq=4, Hkv_self=2, Hkv=2, d=128, n_self=2, n_cross=2, window=64, ffn=512, vocab=500, eps=1e-6)
+    w = ys.stack_weights(21, s, "bf16")
+    T0, steps = 150, 30
+    tok = ys.tokens(22, T0 + steps, s["vocab"])
+    ref8 = oracle.yoco_stack(tok, dict(w, cache_bits=8), "full")
+    ref = oracle.yoco_stack(tok, w, "full")
+    t = torch.from_numpy(tok).cuda()
+    out = {}
+    for name, cdt in (("int8", torch.int8), ("bf16", None)):
+        st = YocoStack(w, torch.bfloat16, cache_dtype=cdt)
+        state = st.new_generation_state(T0 + steps)
+        logits = [host(st.prefill(t[:T0], state))[0]]
+        for i in range(steps):
+            logits.append(host(st.decode_step(t[T0 + i], state))[0])
+        out[name] = np.stack(logits)
+    big = np.abs(ref).max()
+    e8 = np.abs(out["int8"] - ref8[T0 - 1:]).max()
+    e16 = np.abs(out["bf16"] - ref[T0 - 1:]).max()
+    moved = np.abs(ref8 - ref).max()
+    print("stack, coded cache vs its oracle %.3e; uncoded cache vs its oracle %.3e; codes move the oracle's logits by %.3e (scale %.3f)"
+          % (e8, e16, moved, big), flush=True)
+    # bf16 kernels and bf16 K^, V^ rows (coded after that rounding, which can flip a code here and there)
+    assert e8 <= 0.02 * big and e16 <= 0.02 * big
+    assert moved <= 0.02 * big

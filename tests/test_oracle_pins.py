@@ -584,3 +584,21 @@ def test_cross_attn_int8_is_attention_over_the_coded_rows_and_within_its_bound()
     k2, s2 = oracle.kv_quantise_int8(k)
     coarse = oracle.cross_attn(q[-3:], (2 * np.rint(k2 / 2.0)) * s2.astype(np.float64)[..., None], vq, T - 3, scale)
     assert np.abs(coarse - exact).max() > err
+
+
+def test_stack_with_8_bit_cache_keeps_the_generation_and_early_exit_invariants():
+    """cache_bits = 8 changes K^, V^ to their coded values and nothing else: early exit still equals the last row of
+    the full forward, token-by-token generation still equals the all-at-once forward (rows are coded one by one, each
+    with its own scale), and the logits move by little but not by nothing."""
+    c = ys.CONFIGS["tiny_fp32"]
+    s = dict(c["stack"], n_self=1, n_cross=2)
+    w = ys.stack_weights(3, s, "f32")
+    tok = ys.tokens(5, 40, s["vocab"])
+    plain = oracle.yoco_stack(tok, w, "full")
+    w8 = dict(w, cache_bits=8)
+    full = oracle.yoco_stack(tok, w8, "full")
+    np.testing.assert_allclose(oracle.yoco_stack(tok, w8, "early_exit")[0], full[-1], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(oracle.yoco_stack_generate(tok, w8), full, rtol=0, atol=1e-10)
+    diff = np.abs(full - plain).max()
+    assert 0 < diff < 0.02 * np.abs(plain).max()
+    np.testing.assert_allclose(full[0], oracle.yoco_stack(tok[:1], w8, "full")[0], rtol=0, atol=1e-12)   # still a decoder-only model
