@@ -1,8 +1,8 @@
 """The generation calls are plain kernel launches on the caller's stream (no
 allocation, no memset, no synchronisation), so a decode step can be captured
 into a HIP graph. One step of a 3 + 3-layer stack's attention (rolling-window
-append + decode, gated-retention decode, global-cache append + split-KV decode)
-is captured once and replayed several times with eager work and
+append + decode, gated-retention decode, global-cache append + split-KV decode,
+the same over an 8-bit global cache) is captured once and replayed several times with eager work and
 synchronisations in between; every replay must reproduce the eager result bit
 for bit."""
 import math
@@ -28,6 +28,9 @@ def test_decode_step_replays_from_a_hip_graph():
     for i, kv in enumerate(rings + [cache]):
         for pl in kv.planes():
             pl.copy_(ys.device_normal(pl.shape, 40 + i, 1.0, bf, dev))
+    cache8 = yoco.KVCache(B, Hkv, d, N, torch.int8)     # the 8-bit variant of the global cache, filled by the write call
+    for b in range(B):
+        yoco.global_kv_write(cache8, ys.device_normal((N, Hkv, d), 50 + b, 1.0, bf, dev), ys.device_normal((N, Hkv, d), 55 + b, 1.0, bf, dev), b, 0)
     states0 = [ys.device_normal((B, H, d, d), 60 + i, 1.0, torch.float32, dev) for i in range(layers)]
     q = [ys.device_normal((B, H, d), 70 + i, 1.0, bf, dev) for i in range(3 * layers)]
     knew = [ys.device_normal((B, H, d), 90 + i, 1.0, bf, dev) for i in range(layers)]
@@ -38,7 +41,8 @@ def test_decode_step_replays_from_a_hip_graph():
     ws_r = torch.empty(yoco.cross_attn_decode_workspace(rings[0], H)[0], dtype=torch.uint8, device=dev)
     ws_c = torch.empty(yoco.cross_attn_decode_workspace(cache, H)[0], dtype=torch.uint8, device=dev)
     states = [s.clone() for s in states0]
-    outs = [torch.empty(B, H, d, dtype=bf, device=dev) for _ in range(3 * layers)]
+    ws_8 = torch.empty(yoco.cross_attn_decode_workspace(cache8, H)[0], dtype=torch.uint8, device=dev)
+    outs = [torch.empty(B, H, d, dtype=bf, device=dev) for _ in range(3 * layers + 1)]
 
     def step():
         for i in range(layers):
@@ -48,6 +52,8 @@ def test_decode_step_replays_from_a_hip_graph():
         yoco.kv_cache_append(cache, khat, khat, pos, False)
         for i in range(layers):
             yoco.cross_attn_decode(cache, q[2 * layers + i], lens, scale, ws_c, out=outs[2 * layers + i])
+        yoco.kv_cache_append(cache8, khat, khat, pos, False)
+        yoco.cross_attn_decode(cache8, q[0], lens, scale, ws_8, out=outs[3 * layers])
 
     def reset():
         for s, s0 in zip(states, states0):

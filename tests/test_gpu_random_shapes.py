@@ -106,6 +106,44 @@ def test_cache_write_prefill_and_decode_random_shape(yoco, seed):
 
 
 @pytest.mark.parametrize("seed", range(12))
+def test_coded_cache_random_shape(yoco, seed):
+    """8-bit global cache: rows written in pieces of mixed source dtypes plus one appended row per sequence, then a
+    decode step and a few exit rows, against the oracle's attention over its own codes of the same rows."""
+    rng = np.random.default_rng(5000 + seed)
+    d = 128
+    Hkv = int(rng.integers(1, 4))
+    Hq = Hkv * int(rng.choice([1, 2, 3, 4]))
+    B = int(rng.integers(1, 4))
+    N_cap = draw_len(rng, 700) + int(rng.integers(0, 300))
+    lens = [int(rng.integers(1, N_cap + 1)) for _ in range(B)]
+    std = float(rng.choice([0.05, 1.0, 6.0]))
+    scale = 1.0 / math.sqrt(d)
+    what = "coded cache %s" % ((B, Hq, Hkv, N_cap, lens, std),)
+    print(what, flush=True)
+    cache = yoco.KVCache(B, Hkv, d, N_cap, torch.int8)
+    cache.mem.fill_(0xFF)
+    K = [ys.normal(rng, (n, Hkv, d), std, "bf16") for n in lens]
+    V = [ys.normal(rng, (n, Hkv, d), std, "bf16") for n in lens]
+    for b, n in enumerate(lens):                       # all rows but the last: two pieces, one given as f32 and one as bf16
+        cut = int(rng.integers(0, n))
+        yoco.global_kv_write(cache, dev(K[b][:cut], "f32"), dev(V[b][:cut], "f32"), b, 0)
+        yoco.global_kv_write(cache, dev(K[b][cut:n - 1], "bf16"), dev(V[b][cut:n - 1], "bf16"), b, cut)
+    pos = torch.tensor([n - 1 for n in lens], dtype=torch.int64, device="cuda")
+    yoco.kv_cache_append(cache, dev(np.stack([K[b][-1] for b in range(B)]), "bf16"), dev(np.stack([V[b][-1] for b in range(B)]), "bf16"),
+                         pos, False)
+    qd = ys.normal(rng, (B, Hq, d), 1.0, "bf16")
+    nbytes, _ = yoco.cross_attn_decode_workspace(cache, Hq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    od = host(yoco.cross_attn_decode(cache, dev(qd, "bf16"), pos + 1, scale, ws))
+    for b, n in enumerate(lens):
+        check(od[b], oracle.cross_attn_int8(qd[b:b + 1], K[b], V[b], n - 1, scale)[0], "bf16", what + " decode b=%d" % b, relative=True)
+        Tq = int(rng.integers(1, min(n, 8) + 1))
+        qp = ys.normal(rng, (Tq, Hq, d), 1.0, "bf16")
+        op = host(yoco.cross_attn_prefill(cache, dev(qp, "bf16"), b, n - Tq, scale, workspace=ws))
+        check(op, oracle.cross_attn_int8(qp, K[b], V[b], n - Tq, scale), "bf16", what + " exit rows b=%d Tq=%d" % (b, Tq), relative=True)
+
+
+@pytest.mark.parametrize("seed", range(12))
 def test_rolling_cache_decode_random_shape(yoco, seed):
     rng = np.random.default_rng(3000 + seed)
     dtype = "bf16" if seed % 2 else "f32"
