@@ -75,6 +75,77 @@ __global__ void __launch_bounds__(256) kv_code_i8_kernel(yoco_kv_cache c, const 
   if (lane == 0) *(float*)(blk + kI8ScaleOffset + 4 * rho) = scale;
 }
 
+// Whole 64-row blocks: one workgroup per (block, KV head, plane), thread (rho = t / 4, part = t % 4) codes dims
+// 32 part .. 32 part + 31 of block row rho. K codes leave as two 16-byte pieces per thread; V codes are transposed
+// through LDS so that they leave as 16-byte pieces too. k, v point at the source row of the first block.
+template <typename S> struct Row32;
+template <> struct Row32<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&x)[32]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const f32x4 a = *(const f32x4*)(p + 4 * i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[4 * i + j] = a[j];
+    }
+  }
+};
+template <> struct Row32<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&x)[32]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x4 a = *(const u32x4*)(p + 8 * i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        x[8 * i + 2 * j] = __uint_as_float(a[j] << 16);
+        x[8 * i + 2 * j + 1] = __uint_as_float(a[j] & 0xffff0000u);
+      }
+    }
+  }
+};
+
+template <typename S>
+__global__ void __launch_bounds__(256) kv_code_i8_block_kernel(yoco_kv_cache c, const S* __restrict__ k, const S* __restrict__ v,
+                                                               int b, int64_t blk0) {
+  __shared__ __attribute__((aligned(16))) unsigned char tile[kI8ScaleOffset];
+  const int t = threadIdx.x, rho = t >> 2, part = t & 3;
+  const int g = blockIdx.y, which = blockIdx.z;
+  const S* src = (which ? v : k) + (((int64_t)blockIdx.x * 64 + rho) * c.Hkv + g) * kD + part * 32;
+  float x[32];
+  Row32<S>::load(src, x);
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) a = fmaxf(a, fabsf(x[i]));
+  a = fmaxf(a, __shfl_xor(a, 1));
+  a = fmaxf(a, __shfl_xor(a, 2));
+  const float inv = a > 0.f ? 127.f / a : 0.f;
+  const float scale = a > 0.f ? a / 127.f : 0.f;
+  int code[32];
+#pragma unroll
+  for (int i = 0; i < 32; ++i) code[i] = (int)fminf(fmaxf(rintf(x[i] * inv), -127.f), 127.f);
+  char* blk = (char*)(which ? c.v : c.k) + ((int64_t)b * c.Hkv + g) * i8_plane_bytes(c.N_cap) + (blk0 + blockIdx.x) * kI8BlockBytes;
+  if (which) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) tile[i8_v_offset(rho, part * 32 + i)] = (unsigned char)(code[i] + 128);
+    __syncthreads();
+    *(u32x4*)(blk + t * 32) = *(const u32x4*)(tile + t * 32);
+    *(u32x4*)(blk + t * 32 + 16) = *(const u32x4*)(tile + t * 32 + 16);
+  } else {
+#pragma unroll
+    for (int piece = 0; piece < 2; ++piece) {
+      u32x4 w;
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4) {
+        unsigned u = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u |= ((unsigned)code[piece * 16 + d4 * 4 + j] & 0xffu) << (8 * j);
+        w[d4] = u;
+      }
+      *(u32x4*)(blk + i8_k_offset(rho, part * 32 + piece * 16)) = w;
+    }
+  }
+  if (part == 0) *(float*)(blk + kI8ScaleOffset + 4 * rho) = scale;
+}
+
 // ---------------------------------------------------------------- decode pass 1 over the coded cache
 // Both contractions run on the matrix cores, whose operands are exactly what the block layout delivers:
 //   scores  S^T[row][head] = K[row][dim] . q[head][dim]      v_mfma_i32_16x16x64_i8, K codes as loaded (no conversion);
@@ -325,13 +396,38 @@ bool decode_i8_supported(const yoco_kv_cache& c, int Hq) {
 
 hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
                              const int64_t* pos, int src_dtype, hipStream_t s) {
-  const int64_t rows = pos ? c.B : n;
-  const int64_t waves = rows * c.Hkv * 2;
-  dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-  if (src_dtype == YOCO_F32)
-    hipLaunchKernelGGL(kv_code_i8_kernel<float>, grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, rows, pos);
-  else
-    hipLaunchKernelGGL(kv_code_i8_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, rows, pos);
+  // rows [r0, r1) of the source, one wavefront per (row, head, plane)
+  auto by_rows = [&](int64_t r0, int64_t r1, int64_t slot0) {
+    if (r1 <= r0) return;
+    const int64_t waves = (r1 - r0) * c.Hkv * 2;
+    const size_t skip = (size_t)r0 * c.Hkv * kD;
+    dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+    if (src_dtype == YOCO_F32)
+      hipLaunchKernelGGL(kv_code_i8_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, b, slot0, r1 - r0, pos);
+    else
+      hipLaunchKernelGGL(kv_code_i8_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, b, slot0, r1 - r0, pos);
+  };
+  if (pos) {                                  // one row per sequence at device-side positions
+    by_rows(0, c.B, 0);
+    return hipGetLastError();
+  }
+  // rows that fill whole 64-row blocks go block by block, the ragged head and tail row by row
+  const int64_t end = pos0 + n;
+  const int64_t first_full = ((pos0 + 63) / 64) * 64, last_full = (end / 64) * 64;
+  if (last_full <= first_full) {
+    by_rows(0, n, pos0);
+    return hipGetLastError();
+  }
+  by_rows(0, first_full - pos0, pos0);
+  {
+    const size_t skip = (size_t)(first_full - pos0) * c.Hkv * kD;
+    dim3 grid((unsigned)((last_full - first_full) / 64), c.Hkv, 2), block(256);
+    if (src_dtype == YOCO_F32)
+      hipLaunchKernelGGL(kv_code_i8_block_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, b, first_full / 64);
+    else
+      hipLaunchKernelGGL(kv_code_i8_block_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, b, first_full / 64);
+  }
+  by_rows(last_full - pos0, n, last_full);
   return hipGetLastError();
 }
 

@@ -202,6 +202,7 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
   if (c->dtype == YOCO_INT8) {
     if (n * c->Hkv > (int64_t)1 << 32) return fail(YOCO_ERR_UNSUPPORTED, "too many rows for one call");
+    if (c->Hkv > 65535) return fail(YOCO_ERR_UNSUPPORTED, "Hkv %d exceeds the grid limit", c->Hkv);
     return hip_result(yoco::launch_kv_code_i8(*c, k, v, b, pos0, n, nullptr, src_dtype, (hipStream_t)stream), "global_kv_write");
   }
   return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, 0, n, src_dtype, (hipStream_t)stream), "global_kv_write");

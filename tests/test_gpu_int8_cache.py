@@ -64,7 +64,8 @@ def spread_rows(rng, shape, dtype):
 
 # ------------------------------------------------------------ coding rows (exact)
 @pytest.mark.parametrize("src", ["f32", "bf16"])
-@pytest.mark.parametrize("N_cap,pos0,n", [(64, 0, 64), (100, 0, 1), (100, 37, 63), (300, 60, 200), (1000, 999, 1), (130, 0, 0)])
+@pytest.mark.parametrize("N_cap,pos0,n", [(64, 0, 64), (100, 0, 1), (100, 37, 63), (300, 60, 200), (1000, 999, 1), (130, 0, 0),
+                                              (1000, 0, 1000), (640, 128, 512), (700, 1, 698)])
 def test_global_kv_write_codes_are_exact(yoco, src, N_cap, pos0, n):
     B, Hkv = 2, 3
     rng = np.random.default_rng(N_cap * 7 + pos0 + n)
