@@ -97,8 +97,8 @@ typedef struct yoco_kv_cache {
  * Every element is off by at most scale / 2 = max|x| / 254. Attention reads the
  * codes: yoco_cross_attn_decode, and yoco_cross_attn_prefill for up to 8 rows
  * with the decode workspace (the exit row of an early-exit prefill); q and o
- * are bf16. head_dim must be 128 and
- * Hq / Hkv at most 4. A rolling window cache cannot be 8-bit.
+ * are bf16. head_dim must be 128 and Hq / Hkv at most 16. A rolling window
+ * cache cannot be 8-bit.
  * Layout of a plane per (sequence, KV head): ceil(N_cap / 64) blocks of 64 rows,
  * 8448 bytes each: 8192 code bytes, then the rows' 64 fp32 scales in row order;
  * 132 bytes per cached token, KV head and plane instead of 256 in bf16. The

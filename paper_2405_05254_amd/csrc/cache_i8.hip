@@ -152,7 +152,8 @@ __global__ void __launch_bounds__(256) kv_code_i8_block_kernel(yoco_kv_cache c, 
 //           q is split into two int8 parts per head, q = s1 * hi + (s1 / 254) * lo, which keeps 16 bits below max|q|
 //   output  O^T[dim][head] += V^T[dim][row] . w[row][head]   v_mfma_f32_16x16x32_f16, V codes turned into exact fp16
 //           integers (2 VALU ops per 4 codes), w = softmax weight * row scale in fp16, kept <= 1 by running its own maximum
-// Lane (n = lane % 16, qg = lane / 16) owns head n (lanes n >= G idle along) and rows 16 qg .. 16 qg + 15 of a block.
+// Lane (n = lane % 16, qg = lane / 16) owns head n (lanes n >= G idle along) and rows 16 qg .. 16 qg + 15 of a block,
+// so up to 16 query heads per KV head cost the same as one.
 __device__ __forceinline__ f16x2 as_f16x2(unsigned x) { return __builtin_bit_cast(f16x2, x); }
 
 // Two code bytes (code + 128) -> two exact fp16 integers: a byte under exponent bits 0x64 is 1024 + byte, then - (1024 + 128).
@@ -176,14 +177,13 @@ struct Block {             // what a lane holds of one 64-row block
   float ks, vs;            // scales of row `lane`: one coalesced 256-byte load per plane
 };
 
-template <int G>
 struct State {
   float m, l, mo;          // running max of the scores, partial sum of weights, running max of score + log2(row scale of V)
   f32x4 o[8];              // O^T[16 t + 4 qg + i][n], relative to 2^mo
 };
 
-template <int G, bool TAIL>
-__device__ __forceinline__ void step(State<G>& st, const i32x4 (&qhi)[2], const i32x4 (&qlo)[2], float qs, const Block& x, int qg,
+template <bool TAIL>
+__device__ __forceinline__ void step(State& st, const i32x4 (&qhi)[2], const i32x4 (&qlo)[2], float qs, const Block& x, int qg,
                                      int nvalid, float (*sc)[64]) {
   // Lane (n, qg) needs the scales of rows 16 qg .. 16 qg + 15: pass them through the wavefront's own LDS lines
   // (a wavefront's LDS operations complete in order, so no barrier is involved).
@@ -248,12 +248,14 @@ __device__ __forceinline__ void step(State<G>& st, const i32x4 (&qhi)[2], const 
 
 // Workgroup = 4 wavefronts on one (sequence, KV head, split); each wavefront walks a contiguous run of blocks,
 // the next block's loads in flight while the current one is reduced. q, o are bf16.
-template <int G>
+// GMAX sizes the merge buffers (4 or 16 heads per KV head); G = Hq / Hkv <= GMAX is the real group size.
+template <int GMAX>
 __global__ void __launch_bounds__(256, 2) decode_i8_kernel(yoco_kv_cache c, const bf16_t* __restrict__ q,
                                                         const int64_t* __restrict__ lens, int64_t fixed_len, int Hq, float scale_log2,
                                                         float* __restrict__ ws, int splits, bf16_t* __restrict__ o_direct) {
-  __shared__ float red_o[4][G][kD];
-  __shared__ float red_ml[4][G][2];
+  __shared__ float red_o[4][GMAX][kD];
+  __shared__ float red_ml[4][GMAX][2];
+  const int G = Hq / c.Hkv;
   __shared__ __attribute__((aligned(16))) float scales[4][2][64];
   const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -315,7 +317,7 @@ __global__ void __launch_bounds__(256, 2) decode_i8_kernel(yoco_kv_cache c, cons
     qs = s2 * scale_log2;
   }
 
-  State<G> st;
+  State st;
   st.m = kNegBig;
   st.mo = kNegBig;
   st.l = 0.f;
@@ -343,9 +345,9 @@ __global__ void __launch_bounds__(256, 2) decode_i8_kernel(yoco_kv_cache c, cons
     for (; row0 + 64 < w_hi; row0 += 64) {
       const Block cur = nx;
       load(row0 + 64);
-      step<G, false>(st, qhi, qlo, qs, cur, qg, 64, scales[wave]);
+      step<false>(st, qhi, qlo, qs, cur, qg, 64, scales[wave]);
     }
-    step<G, true>(st, qhi, qlo, qs, nx, qg, (int)(w_hi - row0), scales[wave]);   // last block of the run, 1..64 rows
+    step<true>(st, qhi, qlo, qs, nx, qg, (int)(w_hi - row0), scales[wave]);   // last block of the run, 1..64 rows
   }
 
   // One state per head and wavefront: gather the partial sums of the four row groups, rebase the output on 2^m.
@@ -391,7 +393,7 @@ bool cache_i8_supported(int d) { return d == kD; }
 bool decode_i8_supported(const yoco_kv_cache& c, int Hq) {
   if (c.dtype != YOCO_INT8 || c.d != kD) return false;
   const int G = Hq / c.Hkv;
-  return G >= 1 && G <= 4 && c.Hkv <= 65535;
+  return G >= 1 && G <= 16 && c.Hkv <= 65535;
 }
 
 hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
@@ -437,13 +439,12 @@ hipError_t launch_decode_i8(const yoco_kv_cache& c, const void* q, const int64_t
   dim3 grid(splits, c.Hkv, c.B), block(256);
   const float sl2 = scale * kLog2e;
   const bf16_t* qp = (const bf16_t*)q;
-  switch (Hq / c.Hkv) {
-    case 1: hipLaunchKernelGGL(decode_i8_kernel<1>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 2: hipLaunchKernelGGL(decode_i8_kernel<2>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 3: hipLaunchKernelGGL(decode_i8_kernel<3>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    case 4: hipLaunchKernelGGL(decode_i8_kernel<4>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od); break;
-    default: return hipErrorInvalidValue;
-  }
+  const int G = Hq / c.Hkv;
+  if (G < 1 || G > 16) return hipErrorInvalidValue;
+  if (G <= 4)
+    hipLaunchKernelGGL(decode_i8_kernel<4>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od);
+  else
+    hipLaunchKernelGGL(decode_i8_kernel<16>, grid, block, 0, s, c, qp, lens, fixed_len, Hq, sl2, ws, splits, od);
   return hipGetLastError();
 }
 

@@ -90,7 +90,7 @@ int run_decode(const yoco_kv_cache& c, const void* q, void* o, const int64_t* le
   hipError_t e;
   if (c.dtype == YOCO_INT8) {
     if (!yoco::decode_i8_supported(c, Hq))
-      return fail(YOCO_ERR_UNSUPPORTED, "%s: an 8-bit cache serves up to 4 query heads per KV head, not %d", what, Hq / c.Hkv);
+      return fail(YOCO_ERR_UNSUPPORTED, "%s: an 8-bit cache serves up to 16 query heads per KV head, not %d", what, Hq / c.Hkv);
     if (k_new) return fail(YOCO_ERR_UNSUPPORTED, "%s: no fused append into an 8-bit cache", what);
     e = yoco::launch_decode_i8(c, q, lens, fixed_len, Hq, scale, ws, splits, o, s);
     if (splits == 1) return hip_result(e, what);

@@ -217,7 +217,7 @@ def test_eight_bit_cache_sizes_and_validation():
     assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 50, 4, 1.0, None, 0, None) == -2
     assert L.yoco_cross_attn_prefill(C.byref(d), p, p, 0, 0, 2, 4, 1.0, None, 0, None) == -2
     assert b"8-bit" in L.yoco_last_error_string()
-    # more than 4 query heads per KV head: refused before any launch
-    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 10, C.byref(ws), C.byref(s)) == 0
-    assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 10, 1.0, p, ws.value, None) == -2
+    # more than 16 query heads per KV head: refused before any launch
+    assert L.yoco_cross_attn_decode_workspace(C.byref(d), 34, C.byref(ws), C.byref(s)) == 0
+    assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 34, 1.0, p, ws.value, None) == -2
     assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 4, 1.0, p, 16, None) == -4

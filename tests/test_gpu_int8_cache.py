@@ -152,7 +152,7 @@ def decode_case(yoco, seed, B, Hq, Hkv, N_cap, lens, std=1.0, blocks=None, monke
     return o
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (6, 2), (8, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (6, 2), (8, 2), (10, 2), (16, 2), (32, 2), (13, 1)])
 def test_decode_over_codes_every_group_size(yoco, Hq, Hkv):
     decode_case(yoco, 100 + Hq, 3, Hq, Hkv, 700, [700, 333, 64])
 

@@ -112,7 +112,7 @@ def test_coded_cache_random_shape(yoco, seed):
     rng = np.random.default_rng(5000 + seed)
     d = 128
     Hkv = int(rng.integers(1, 4))
-    Hq = Hkv * int(rng.choice([1, 2, 3, 4]))
+    Hq = Hkv * int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
     B = int(rng.integers(1, 4))
     N_cap = draw_len(rng, 700) + int(rng.integers(0, 300))
     lens = [int(rng.integers(1, N_cap + 1)) for _ in range(B)]
