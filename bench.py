@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes of one SWA prefill launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) of `bench.py --only swa`, each scaled by what the counter reads for a 1 GiB copy (`--only calib`:
 # FETCH_SIZE reads 0.5 GiB -> factor 2.0, WRITE_SIZE reads 1.0 GiB -> factor 1.0). See profiles/.
-SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308484.0 * 1024, "write": 1.0 * 198078.3 * 1024}
+SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308514.2 * 1024, "write": 1.0 * 198132.5 * 1024}
 
 
 def swa_flops(T, H, d, C):
