@@ -346,6 +346,19 @@ def test_cache_arithmetic_matches_paper_numbers():
     assert per_tok_tf / per_tok == vals["reduction_factor"]
 
 
+def test_8_bit_cache_arithmetic_matches_the_papers_65b_example():
+    vals = {}
+    with open(os.path.join(HERE, "golden", "kv_cache_65b_512k_8bit.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = int(v)
+    per_tok = oracle.kv_cache_bytes_per_token(vals["kv_heads"], vals["head_dim"], vals["elem_bytes"], cached_layers=vals["layers"])
+    assert round(per_tok * vals["tokens"] / 1e9) == vals["gigabytes_rounded"]
+    # the same model with YOCO's single global pair needs 1/80 of that
+    assert per_tok // oracle.kv_cache_bytes_per_token(vals["kv_heads"], vals["head_dim"], vals["elem_bytes"]) == vals["layers"]
+
+
 # ---------------------------------------------------------------- input module
 def test_bf16_rounding_is_rne_and_idempotent():
     x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.1415927, 1e-30, 65504.0], dtype=np.float32)
