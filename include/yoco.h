@@ -128,6 +128,12 @@ int yoco_kv_cache_init(void* mem, size_t bytes, int B, int Hkv, int d, int64_t N
  * (the mask  i - C < j <= i : a row sees itself and the window-1 keys before).
  * q, o: [B,T,Hq,d]; k, v: [B,T,Hkv,d]; all of `dtype`. window >= 1; a window
  * >= T is plain causal attention.
+ * Domain of the bf16, d = 128 matrix-core path: the softmax weights and V enter
+ * the second product as fp16 (fp32 accumulation), so |v| must stay below 65504
+ * (a larger bf16 value becomes infinite there); |v| under 2^-14 loses low bits
+ * or flushes to zero, an absolute error below 2^-25 per element. q and k have
+ * no such limit (bf16 products, exact in fp32). fp32 inputs, other head
+ * dimensions and scale <= 0 run on fp32 vector kernels without this limit.
  */
 int yoco_swa_prefill(const void* q, const void* k, const void* v, void* o, int B, int64_t T, int Hq,
                      int Hkv, int d, int64_t window, float scale, int dtype, void* stream);
@@ -154,6 +160,9 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
  * (the exit row of an early-exit prefill, Fig. 3) is split over the cache like
  * a decode step instead of walking it with one workgroup per head. The result
  * is the same operation either way.
+ * A bf16 cache with d = 128 and more than 8 rows runs on the same matrix-core
+ * path as yoco_swa_prefill, with the same domain: cached |v| below 65504, and
+ * |v| under 2^-14 read with an absolute error below 2^-25.
  */
 int yoco_cross_attn_prefill(const yoco_kv_cache* c, const void* q, void* o, int b, int64_t q_pos0,
                             int64_t Tq, int Hq, float scale, void* workspace, size_t workspace_bytes,

@@ -389,19 +389,29 @@ def cross_attn_int8(Q, Khat, Vhat, q_pos0, scale):
 
 
 def cross_attn_int8_error_bound(Q, Khat, Vhat, scale):
-    """An upper bound on |cross_attn_int8 - cross_attn| for every output element.
+    """A tight upper bound on |cross_attn_int8 - cross_attn| for every output element.
 
     Every element of a row moves by at most half a code step, h = max|row|/254
-    (plus float32 rounding of the scale, covered by the 1.001). A score moves by
-    at most D = scale * max_i ||q_i||_1 * max_j h(k_j); each softmax weight then
-    changes by a factor within exp(+-2D), and the output is a convex combination
-    of V rows, so the total is  max_j h(v_j) + (exp(2D) - 1) * max|V^|.
+    (plus float32 rounding of the scale, covered by the 1.001), and a coded
+    value never exceeds its row's maximum. With O = sum_j p_j v_j over the
+    exact rows and O' = sum_j p'_j v'_j over the coded ones,
+        O' - O = sum_j p'_j (v'_j - v_j) + sum_j (p'_j - p_j) v_j.
+    The first sum is a convex combination of V moves: at most hv = max_j h(v_j).
+    For the second, a score moves by at most D = scale * max_i ||q_i||_1 *
+    max_j h(k_j), so p'_j is proportional to p_j * exp(delta_j) with |delta_j| <= D;
+    the total variation between two such distributions is largest when a set of
+    weight 1/(1 + e^D) moves up by D and the rest down by D, where it equals
+    tanh(D/2), so sum_j |p'_j - p_j| <= 2 tanh(D/2). Total:
+        hv + 2 tanh(D/2) max|V^|.
+    Both terms are attained (rows sitting half a step off their codes), which is
+    what the pins use to hold the bound from above and from below.
     """
     Q = np.asarray(Q, dtype=F64)
+    vmax = np.abs(np.asarray(Vhat, dtype=F64)).max()
     hk = 1.001 * np.abs(np.asarray(Khat, dtype=F64)).max() / 254.0
-    hv = 1.001 * np.abs(np.asarray(Vhat, dtype=F64)).max() / 254.0
+    hv = 1.001 * vmax / 254.0
     D = scale * np.abs(Q).sum(axis=-1).max() * hk
-    return hv + np.expm1(2.0 * D) * (np.abs(np.asarray(Vhat, dtype=F64)).max() + hv)
+    return hv + 2.0 * np.tanh(0.5 * D) * vmax
 
 
 def kv_cache_bytes_per_token(Hkv, d, elem_bytes, cached_layers=1):

@@ -19,8 +19,8 @@ class _Cache(C.Structure):
 
 
 def lib_path():
-    """In-tree libyoco.so; YOCO_LIB_PATH names another build of the same library (development aid)."""
-    return os.environ.get("YOCO_LIB_PATH") or os.path.join(_PKG, "libyoco.so")
+    """The in-tree libyoco.so (the only build this binding loads)."""
+    return os.path.join(_PKG, "libyoco.so")
 
 
 def lib():
@@ -81,6 +81,27 @@ def _dev(t, name):
     return t.data_ptr()
 
 
+def _out(out, like, name="out"):
+    """The output tensor: a fresh one shaped like `like`, or the caller's, which must be exactly that tensor's
+    shape, dtype and device (the C ABI sees only a pointer and would write past a shorter or narrower buffer)."""
+    if out is None:
+        return torch.empty_like(like, memory_format=torch.contiguous_format)
+    if out.shape != like.shape or out.dtype != like.dtype or out.device != like.device:
+        raise YocoError("%s must be %s %s on %s, got %s %s on %s" % (name, tuple(like.shape), like.dtype, like.device,
+                                                                    tuple(out.shape), out.dtype, out.device))
+    return out
+
+
+def _ws(workspace):
+    """(pointer, bytes) of an optional workspace tensor on the current device."""
+    if workspace is None:
+        return None, 0
+    ptr = _dev(workspace, "workspace")
+    if workspace.device.index != torch.cuda.current_device():
+        raise YocoError("workspace must live on the current device")
+    return ptr, workspace.numel() * workspace.element_size()
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -134,7 +155,7 @@ def swa_prefill(q, k, v, window, scale, out=None):
     Hkv = k.shape[2]
     if k.shape != (B, T, Hkv, d) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
         raise YocoError("q/k/v shapes or dtypes disagree")
-    o = torch.empty_like(q) if out is None else out
+    o = _out(out, q)
     _check(lib().yoco_swa_prefill(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(o, "o"), B, T, Hq, Hkv, d,
                                   window, scale, _dtype(q), _stream()))
     return o
@@ -155,9 +176,8 @@ def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None, workspace=None):
     Tq, Hq, d = q.shape
     if d != cache.d or q.dtype != cache.io_dtype:
         raise YocoError("q does not match the cache")
-    o = torch.empty_like(q) if out is None else out
-    ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
-    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    o = _out(out, q)
+    ws_ptr, ws_bytes = _ws(workspace)
     _check(lib().yoco_cross_attn_prefill(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), b, q_pos0, Tq, Hq, scale,
                                          ws_ptr, ws_bytes, _stream()))
     return o
@@ -176,10 +196,9 @@ def cross_attn_decode(cache, q, lens, scale, workspace, out=None):
         raise YocoError("q does not match the cache")
     if lens.dtype != torch.int64 or lens.shape != (B,):
         raise YocoError("lens must be int64 [B]")
-    o = torch.empty_like(q) if out is None else out
+    o = _out(out, q)
     _check(lib().yoco_cross_attn_decode(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq,
-                                        scale, _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
-                                        _stream()))
+                                        scale, *_ws(workspace), _stream()))
     return o
 
 
@@ -216,10 +235,10 @@ def swa_decode(ring, q, lens, scale, workspace, out=None, k_new=None, v_new=None
     if k_new is not None and (k_new.shape != (B, ring.Hkv, d) or v_new.shape != k_new.shape or k_new.dtype != ring.dtype
                               or v_new.dtype != ring.dtype):
         raise YocoError("k_new/v_new do not match the cache")
-    o = torch.empty_like(q) if out is None else out
+    o = _out(out, q)
     _check(lib().yoco_swa_decode(C.byref(ring.desc), _dev(q, "q"), _dev(k_new, "k_new") if k_new is not None else None,
                                  _dev(v_new, "v_new") if v_new is not None else None, _dev(o, "o"), _dev(lens, "lens"), Hq, scale,
-                                 _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()))
+                                 *_ws(workspace), _stream()))
     return o
 
 
@@ -250,9 +269,8 @@ def gret_prefill(q, k, v, log_gamma, scale, chunk=256, group_norm=True, eps=1e-6
         raise YocoError("log_gamma must be float32 [B,T,H]")
     if gate is not None and (gate.shape != v.shape or gate.dtype != v.dtype):
         raise YocoError("gate must match v")
-    o = torch.empty_like(v) if out is None else out
-    ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
-    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    o = _out(out, v)
+    ws_ptr, ws_bytes = _ws(workspace)
     _check(lib().yoco_gret_prefill(_dev(q, "q") if T else None, _dev(k, "k") if T else None, _dev(v, "v") if T else None,
                                    _dev(log_gamma, "log_gamma") if T else None,
                                    _dev(gate, "gate") if (T and gate is not None) else None, _dev(o, "o") if T else None,
@@ -273,7 +291,7 @@ def gret_decode(q, k, v, log_gamma, state, scale, group_norm=True, eps=1e-6, out
         raise YocoError("log_gamma must be float32 [B,H]")
     if gate is not None and (gate.shape != v.shape or gate.dtype != v.dtype):
         raise YocoError("gate must match v")
-    o = torch.empty_like(v) if out is None else out
+    o = _out(out, v)
     _check(lib().yoco_gret_decode(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(log_gamma, "log_gamma"),
                                   _dev(gate, "gate") if gate is not None else None, _dev(o, "o"),
                                   _state(state, "state", B, H, dk, dv), B, H, dk, dv, scale, int(bool(group_norm)), eps,

@@ -195,6 +195,11 @@ __device__ __forceinline__ void step(State& st, const i32x4 (&qhi)[2], const i32
   for (int i = 0; i < 4; ++i) {
     ks[i] = *(const f32x4*)&sc[0][qg * 16 + i * 4];
     vs[i] = *(const f32x4*)&sc[1][qg * 16 + i * 4];
+    if (TAIL) {   // rows past the end hold whatever the memory held (NaN bits included): zero their scales before any arithmetic
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (qg * 16 + i * 4 + j >= nvalid) { ks[i][j] = 0.f; vs[i][j] = 0.f; }
+    }
   }
   float s[16], t[16];
   float smax = -INFINITY, tmax = -INFINITY;
@@ -210,7 +215,7 @@ __device__ __forceinline__ void step(State& st, const i32x4 (&qhi)[2], const i32
       const int r = tau * 4 + i;
       float a = (float)(__mul24(hi[i], 254) + lo[i]) * (ks[tau][i] * qs);   // |hi| < 2^21
       float b = a + __builtin_amdgcn_logf(vs[tau][i]);               // log2; a zero row of V gets -inf, weight 0
-      if (TAIL && (qg * 16 + r >= nvalid)) { a = -INFINITY; b = -INFINITY; }   // also discards what unwritten scales hold
+      if (TAIL && (qg * 16 + r >= nvalid)) { a = -INFINITY; b = -INFINITY; }   // rows past the end get weight 0
       s[r] = a;
       t[r] = b;
       smax = fmaxf(smax, a);

@@ -56,8 +56,8 @@ int check_heads(int Hq, int Hkv) {
 // Splits of the decode pass. Streaming reads on MI355X are fastest with few,
 // long, contiguous streams: one workgroup per CU, each of its wavefronts
 // walking its own contiguous range (measured: 6.9 TB/s at 256 workgroups,
-// 6.0 TB/s at 2048). At least 512 rows per split.
-// YOCO_DECODE_BLOCKS overrides the workgroup target (tuning aid).
+// 6.0 TB/s at 2048). At least 512 rows per split. A pure function of the
+// cache shape and the device: the workspace query and the decode call agree.
 int decode_splits(const yoco_kv_cache* c) {
   static const int cus = [] {                     // initialised once, thread-safe
     int dev = 0, n = 0;
@@ -66,11 +66,7 @@ int decode_splits(const yoco_kv_cache* c) {
     (void)hipGetLastError();
     return ok ? n : 256;                          // no device visible (host-only sizing): MI355X has 256 CUs
   }();
-  int64_t target = cus;
-  if (const char* e = getenv("YOCO_DECODE_BLOCKS")) {
-    const long v = atol(e);
-    if (v > 0) target = v;
-  }
+  const int64_t target = cus;
   const int64_t units = (int64_t)c->B * c->Hkv;
   int64_t s = (target + units - 1) / units;
   const int64_t by_rows = (c->N_cap + 511) / 512;

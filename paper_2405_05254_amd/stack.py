@@ -39,7 +39,7 @@ class YocoStack:
     def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32, cache_dtype=None):
         self.dtype, self.device, self.glue = dtype, device, glue_dtype
         self.cache_dtype = dtype if cache_dtype is None else cache_dtype   # torch.int8: the global cache holds 8-bit codes
-        self.capture = None          # dict layer-name -> (q, k, v, o) when set by a test
+        self.capture = None          # dict layer-name -> (q, k, v, o) (gated retention: + log-decays, gate) when set by a test
 
         def dev(a):
             return torch.as_tensor(a).to(device=device, dtype=glue_dtype)
@@ -82,13 +82,15 @@ class YocoStack:
                 o = yb.gret_prefill(q, k, v, lg, self.scale, chunk=256, group_norm=True, eps=self.eps,
                                     state_out=None if rings is None else rings[n], workspace=ws, gate=gate)
                 a = o.view(T, self.Hq * self.d).to(self.glue)
+                if self.capture is not None and ("self%d" % n) in self.capture:
+                    self.capture["self%d" % n] = (q[0], k[0], v[0], o[0], lg[0], gate[0])
                 del ws, lg, gate
             else:
                 o = yb.swa_prefill(q, k, v, self.window, self.scale)
                 if rings is not None:
                     yb.swa_cache_write(rings[n], k[0], v[0], 0, 0)
                 a = o.view(T, self.Hq * self.d).to(self.glue)
-            if self.capture is not None and ("self%d" % n) in self.capture:
+            if self.capture is not None and self.self_kind != "gret" and ("self%d" % n) in self.capture:
                 self.capture["self%d" % n] = (q[0], k[0], v[0], o[0])
             Y = a @ L["W_O"] + X
             del q, k, v, o, xn, a

@@ -26,8 +26,9 @@ def pytest_collection_modifyitems(config, items):
 
 @pytest.fixture(scope="session", autouse=True)
 def _libyoco_built():
-    """Load the in-tree libyoco.so; build it first only if nothing is built yet."""
-    from paper_2405_05254_amd import binding, build
-    if not os.path.exists(binding.lib_path()):
+    """Load the in-tree libyoco.so. It is rebuilt first when it is missing or was built from other sources than the
+    tree holds now (a hash of the sources is stored beside it), so the tests never describe a stale library."""
+    from paper_2405_05254_amd import build
+    if not build.is_current():
         build.build_lib()
     yield

@@ -285,26 +285,59 @@ def test_tiny_gret_stack_matches_oracle(yoco):
 
 def test_bf16_gret_stack_early_exit_and_generation(yoco):
     """The end-to-end architecture with a gated-retention self-decoder (d_model 2048, 16 x 128 heads, reduced to
-    3 + 3 layers) at T = 3000, bf16: the chunkwise MFMA path in the prefill. Early exit against the GPU full
-    forward (Fig. 3: same kernels on both sides, 1e-3), and a prompt + decode run against the full forward's rows.
-    The decode steps run the recurrent kernel where the full forward ran the chunkwise one: the two agree to one
-    bf16 rounding of each attention output (2^-9 relative, checked kernel against kernel above), but a rounding
-    that falls differently in layer 1 is carried and amplified through the remaining layers of a random-init
-    stack. This is a check against gross errors (a wrong state hand-over, a missed row), with a bound of 5 % of
-    the largest logit over the 9 x 4096 logits compared (the measured difference is 1-2 %); the fp32 stack above
-    pins the same flow to 1e-3 absolute against the oracle."""
+    3 + 3 layers) at T = 3000, bf16: the chunkwise MFMA path in the prefill. Three checks:
+    (1) early exit against the GPU full forward (Fig. 3: same kernels on both sides, 1e-3);
+    (2) at the attention boundary, layer by layer and teacher-forced: the chunkwise prefill of the first T - 8 rows
+        followed by 8 recurrent decode steps, fed the full forward's own q, k, v, decays and gates of that layer,
+        must reproduce the full forward's attention outputs of the last 8 rows to the bf16 bounds (both sides round
+        the same fp32 value once; the carried state differs by the chunkwise path's fp16-operand rounding);
+    (3) free-running: a prompt + 8 decode steps against the full forward's logits. Here a rounding that falls
+        differently in one layer changes the inputs of the next, whose bf16 roundings (q, k, v, gate, o: ulp 2^-8)
+        then flip with a probability that grows with the incoming difference: a random walk over about 6 layers x 5
+        rounded tensors of steps of about 2e-3 of the values' scale, i.e. about sqrt(30) * 2e-3 = 1.1e-2 of the logit
+        scale in the worst of the 9 x 4096 logits compared (measured 1-2 %). The bound is 5 % of the largest logit:
+        a check against gross errors (a wrong state hand-over, a missed row costs far more); the fp32 stack above
+        pins the same flow to 1e-3 absolute against the oracle, and (2) holds the kernels to the bf16 bounds."""
     from paper_2405_05254_amd.stack import YocoStack
+    import paper_2405_05254_amd as yb
     c = ys.CONFIGS["e2e_early_exit_128k"]
     s = dict(c["stack"], n_self=3, n_cross=3, vocab=4096, self_kind="gret", tau=16.0)
     T = 3000
     w = ys.stack_weights(c["seed"], s, "bf16")
     tok = torch.from_numpy(ys.tokens(c["seed"], T, s["vocab"])).cuda()
     st = YocoStack(w, torch.bfloat16)
+    st.capture = {"self%d" % n: None for n in range(3)}
     full = host(st.forward_full(tok, rows=slice(T - 9, T)))
+    caps = dict(st.capture)
+    st.capture = None
     ee = host(st.forward_early_exit(tok)[0])
     err = np.abs(ee - full[-1:]).max()
     print("bf16 gret stack early-exit vs full: %.3e (logit scale %.3f)" % (err, np.abs(full).max()), flush=True)
     assert err <= 1e-3
+    # (2) the attention boundary, teacher-forced
+    H, d, Tp = st.Hq, st.d, T - 8
+    for n in range(3):
+        q, k, v, o, lg, gate = caps["self%d" % n]
+        state = torch.zeros(1, H, d, d, dtype=torch.float32, device="cuda")
+        nbytes = yb.gret_prefill_workspace(1, Tp, H, d, d, 256, yb.BF16)
+        assert nbytes > 0                                    # the chunkwise path, not the recurrence
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        o_pre = yb.gret_prefill(q[None, :Tp].contiguous(), k[None, :Tp].contiguous(), v[None, :Tp].contiguous(),
+                                lg[None, :Tp].contiguous(), st.scale, chunk=256, group_norm=True, eps=st.eps, state_out=state,
+                                workspace=ws, gate=gate[None, :Tp].contiguous())
+        assert torch.equal(o_pre[0, :Tp - 256], o[:Tp - 256])   # rows of chunks the shorter call shares: the same launches
+        steps = []
+        for i in range(Tp, T):
+            steps.append(yb.gret_decode(q[i][None].contiguous(), k[i][None].contiguous(), v[i][None].contiguous(),
+                                        lg[i][None].contiguous(), state, st.scale, group_norm=True, eps=st.eps,
+                                        gate=gate[i][None].contiguous())[0])
+        got, ref = host(torch.stack(steps)), host(o[Tp:])
+        stt = ys.error_stats(got, ref)
+        print("bf16 gret stack layer %d, prefill + 8 decode steps vs full forward at the attention output: max_abs %.3e mean_rel %.3e"
+              % (n, stt["max_abs"], stt["mean_rel"]), flush=True)
+        big = max(1.0, float(np.abs(ref).max()))
+        assert stt["max_abs"] <= ys.TOL["bf16"]["max_abs"] * big and stt["mean_rel"] <= ys.TOL["bf16"]["mean_rel"], stt
+    # (3) free-running generation
     state = st.new_generation_state(T)
     logits = [host(st.prefill(tok[:T - 8], state))[0]]
     for i in range(T - 8, T):

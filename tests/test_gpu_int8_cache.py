@@ -116,11 +116,9 @@ def test_append_codes_rows_at_device_positions(yoco):
 
 
 # ------------------------------------------------------------ attention over the codes
-def decode_case(yoco, seed, B, Hq, Hkv, N_cap, lens, std=1.0, blocks=None, monkeypatch=None):
+def decode_case(yoco, seed, B, Hq, Hkv, N_cap, lens, std=1.0, want_splits=None):
     scale = 1.0 / math.sqrt(D)
     rng = np.random.default_rng(seed)
-    if blocks is not None:
-        monkeypatch.setenv("YOCO_DECODE_BLOCKS", str(blocks))
     cache = yoco.KVCache(B, Hkv, D, N_cap, torch.int8)
     cache.mem.fill_(0xFF)                                   # unwritten scales read as NaN: masked rows must not leak
     K = ys.normal(rng, (B, N_cap, Hkv, D), std, "bf16")
@@ -131,6 +129,8 @@ def decode_case(yoco, seed, B, Hq, Hkv, N_cap, lens, std=1.0, blocks=None, monke
         if n:
             yoco.global_kv_write(cache, dev(K[b, :n], "bf16"), dev(V[b, :n], "bf16"), b, 0)
     nbytes, splits = yoco.cross_attn_decode_workspace(cache, Hq)
+    if want_splits is not None:
+        assert splits == want_splits, (splits, want_splits)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     o = host(yoco.cross_attn_decode(cache, dev(q, "bf16"), torch.tensor(lens, dtype=torch.int64, device="cuda"), scale, ws))
     assert np.isfinite(o).all()
@@ -161,9 +161,16 @@ def test_decode_over_codes_ragged_lengths_and_block_edges(yoco):
     decode_case(yoco, 7, 10, 6, 2, 520, [0, 1, 63, 64, 65, 255, 256, 257, 520, 9999])
 
 
-@pytest.mark.parametrize("blocks", [1, 8, 64, 1024])
-def test_decode_over_codes_any_split_count(yoco, blocks, monkeypatch):
-    decode_case(yoco, 20 + blocks, 2, 6, 2, 5000, [5000, 1234], blocks=blocks, monkeypatch=monkeypatch)
+@pytest.mark.parametrize("B,Hkv,N_cap,lens,splits", [
+    (2, 2, 500, [500, 123], 1),              # a cache of under 512 rows is never split
+    (2, 2, 5000, [5000, 1234], 10),          # ceil(5000 / 512) rows-limited splits
+    (1, 1, 40000, [40000], 79),
+    (1, 1, 140000, [139999], 256),           # one workgroup per CU: the most a launch uses
+])
+def test_decode_over_codes_any_split_count(yoco, B, Hkv, N_cap, lens, splits):
+    """The split count follows from the shape (one workgroup per CU, at least 512 rows per split): shapes that give
+    1, 10, 79 and 256 splits, ragged last splits included."""
+    decode_case(yoco, 20 + splits, B, 3 * Hkv, Hkv, N_cap, lens, want_splits=splits)
 
 
 def test_decode_over_codes_large_and_small_magnitudes(yoco):

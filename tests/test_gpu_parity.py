@@ -87,6 +87,65 @@ def test_swa_scale_zero_and_negative_use_the_generic_path(yoco):
         check(host(o[0]), oracle.swa(qn, kn, vn, C, scale), "bf16", "swa scale %g" % scale)
 
 
+def check_scaled(got, ref, what):
+    """bf16 bounds with the absolute one scaled by the output's magnitude (the output's own rounding grows with it)."""
+    st = ys.error_stats(got, ref)
+    tol = ys.TOL["bf16"]
+    big = max(1.0, float(np.abs(ref).max()))
+    print("%s: max_abs %.3e (outputs up to %.3e) mean_rel %.3e" % (what, st["max_abs"], big, st["mean_rel"]), flush=True)
+    assert np.isfinite(got).all(), what
+    assert st["max_abs"] <= tol["max_abs"] * big and st["mean_rel"] <= tol["mean_rel"], (what, st)
+
+
+def edge_values(seed, shape, kind):
+    """V tensors at the two ends of the matrix-core path's documented domain, inside it: 'large' has |v| up to 6e4
+    (fp16's largest finite value is 65504), 'small' has |v| around 1e-4, most of it above fp16's smallest normal 2^-14
+    and part of it below (those elements lose low bits, at most 2^-25 each)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal(shape).astype(np.float32)
+    if kind == "large":
+        v = ys.round_to(np.clip(x * np.float32(2.0e4), -6.0e4, 6.0e4), "bf16")
+        assert np.abs(v).max() < 65504 and np.abs(v).max() > 5.9e4
+    else:
+        v = ys.round_to(x * np.float32(1.0e-4), "bf16")
+        assert 0 < (np.abs(v) < 2.0 ** -14).mean() < 0.6
+    return v
+
+
+@pytest.mark.parametrize("kind", ["large", "small"])
+def test_swa_prefill_at_the_edges_of_the_fp16_value_domain(yoco, kind):
+    T, Hq, Hkv, d, C = 700, 4, 2, 128, 200
+    scale = 1.0 / math.sqrt(d)
+    qn, kn, _ = ys.qkv(300, T, Hq, Hkv, d, 1.0, "bf16")
+    vn = edge_values(301, (T, Hkv, d), kind)
+    o = yoco.swa_prefill(dev(qn[None], "bf16"), dev(kn[None], "bf16"), dev(vn[None], "bf16"), C, scale)
+    torch.cuda.synchronize()
+    ref = oracle.swa(qn, kn, vn, C, scale)
+    if kind == "large":
+        check_scaled(host(o[0]), ref, "swa |v| up to 6e4")
+    else:                                                # compare in units of 1e-4 so that the bf16 bounds apply as they stand
+        check(host(o[0]) * 1e4, ref * 1e4, "bf16", "swa |v| ~ 1e-4")
+
+
+@pytest.mark.parametrize("kind", ["large", "small"])
+def test_cross_attn_prefill_at_the_edges_of_the_fp16_value_domain(yoco, kind):
+    Hq, Hkv, d, N, Tq = 6, 2, 128, 900, 400
+    scale = 1.0 / math.sqrt(d)
+    cache = yoco.KVCache(1, Hkv, d, N, torch.bfloat16)
+    cache.mem.zero_()
+    kn = ys.normal(np.random.default_rng(310), (N, Hkv, d), 1.0, "bf16")
+    vn = edge_values(311, (N, Hkv, d), kind)
+    yoco.global_kv_write(cache, dev(kn, "bf16"), dev(vn, "bf16"), 0, 0)
+    qn = ys.normal(np.random.default_rng(312), (Tq, Hq, d), 1.0, "bf16")
+    o = yoco.cross_attn_prefill(cache, dev(qn, "bf16"), 0, N - Tq, scale)
+    torch.cuda.synchronize()
+    ref = oracle.cross_attn(qn, kn, vn, N - Tq, scale)
+    if kind == "large":
+        check_scaled(host(o), ref, "cross prefill |v| up to 6e4")
+    else:
+        check(host(o) * 1e4, ref * 1e4, "bf16", "cross prefill |v| ~ 1e-4")
+
+
 def test_swa_prefill_headline_shape_sampled(yoco):
     """T=32768, 24 heads, d=128, window 1024 (the benchmark's launch), checked on
     sampled (row, head) outputs including the window and tile edges."""

@@ -281,3 +281,56 @@ def test_the_unmutated_quantiser_and_the_oracle_pass():
 @pytest.mark.parametrize("name", sorted(QUANT_MUTANTS))
 def test_pins_catch_planted_quantiser_mistake(name):
     assert not quantiser_battery(make_quantiser(**QUANT_MUTANTS[name])), name
+
+
+# ---------------------------------------------------------------- 8-bit cache: the error bound
+def make_int8_bound(step_div=254.0, weight_term=lambda D: 2.0 * np.tanh(0.5 * D), q_norm=lambda Q: np.abs(Q).sum(axis=-1).max(),
+                    v_step=True, v_mag=lambda V: np.abs(V).max(), use_scale=True):
+    """A copy of the oracle's bound on |attention over codes - attention over the rows| with switches for planted mistakes."""
+    def bound(Q, K, V, scale):
+        Q, K, V = (np.asarray(x, dtype=np.float64) for x in (Q, K, V))
+        hk = 1.001 * np.abs(K).max() / step_div
+        hv = 1.001 * np.abs(V).max() / step_div
+        D = (scale if use_scale else 1.0) * q_norm(Q) * hk
+        return (hv if v_step else 0.0) + weight_term(D) * v_mag(V)
+    return bound
+
+
+def int8_bound_battery(bound):
+    """True if `bound` holds from both sides on the constructed worst cases of tests/test_oracle_pins.py."""
+    from test_oracle_pins import int8_bound_worst_case
+    for D_target in (0.01, 0.05, 0.3):
+        q, K, V, scale = int8_bound_worst_case(D_target)
+        err = np.abs(oracle.cross_attn_int8(q, K, V, 1, scale) - oracle.cross_attn(q, K, V, 1, scale)).max()
+        b = bound(q, K, V, scale)
+        if not (0.90 * b <= err <= b):
+            return False
+    q, K, V, scale = int8_bound_worst_case(0.05)
+    q0 = np.zeros_like(q)
+    err0 = np.abs(oracle.cross_attn_int8(q0, K, V, 1, scale) - oracle.cross_attn(q0, K, V, 1, scale)).max()
+    b0 = bound(q0, K, V, scale)
+    return bool(0.99 * b0 <= err0 <= b0)
+
+
+INT8_BOUND_MUTANTS = {
+    "a whole code step instead of half": dict(step_div=127.0),
+    "a quarter step": dict(step_div=508.0),
+    "weights within exp(+-2D), summed (twice too loose)": dict(weight_term=lambda D: np.expm1(2.0 * D)),
+    "tanh(D/2) without the factor 2": dict(weight_term=lambda D: np.tanh(0.5 * D)),
+    "tanh(D/4)": dict(weight_term=lambda D: 2.0 * np.tanh(0.25 * D)),
+    "largest |q| instead of the 1-norm": dict(q_norm=lambda Q: np.abs(Q).max()),
+    "2-norm of q instead of the 1-norm": dict(q_norm=lambda Q: np.sqrt((Q ** 2).sum(axis=-1)).max()),
+    "V step dropped": dict(v_step=False),
+    "mean |V| instead of the largest": dict(v_mag=lambda V: np.abs(V).mean()),
+    "softmax scale dropped": dict(use_scale=False),
+}
+
+
+def test_the_unmutated_int8_bound_and_the_oracle_pass():
+    assert int8_bound_battery(make_int8_bound())
+    assert int8_bound_battery(oracle.cross_attn_int8_error_bound)
+
+
+@pytest.mark.parametrize("name", sorted(INT8_BOUND_MUTANTS))
+def test_pins_catch_planted_int8_bound_mistake(name):
+    assert not int8_bound_battery(make_int8_bound(**INT8_BOUND_MUTANTS[name])), name

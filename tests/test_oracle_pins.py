@@ -599,6 +599,67 @@ def test_cross_attn_int8_is_attention_over_the_coded_rows_and_within_its_bound()
     assert np.abs(coarse - exact).max() > err
 
 
+def int8_bound_worst_case(D_target=0.05, d=32, t=2.0 ** -7):
+    """Rows built so that both terms of the 8-bit error bound are (almost) attained. Two cache rows, one KV head.
+    K: element 0 = 127 s fixes the row maximum (scale exactly s); the other elements sit 0.499 s above code 10 in
+    row 0 and 0.499 s below it in row 1, so the coded rows are equal and the exact scores differ by
+    scale * ||q||_1 * 0.998 s, q being constant and positive there. V: element 0 = 127 t, the others 0.499 t above code
+    +126 (row 0) and above code -126 (row 1): every coded value is 0.499 t too low and the two rows are almost
+    +-max|V| in the first half of the dims (the second half holds small values). Returns q [1,1,d], K, V [2,1,d] (float32, all values exact) and the scale."""
+    s = np.float32(2.0 ** -5)
+    off = np.float32(0.4990234375)                       # 511/1024: exact in float32 next to small integers
+    K = np.zeros((2, 1, d), dtype=np.float32)
+    K[:, 0, 0] = 127 * s
+    K[0, 0, 1:] = (10 + off) * s
+    K[1, 0, 1:] = (10 - off) * s
+    V = np.zeros((2, 1, d), dtype=np.float32)
+    V[:, 0, 0] = 127 * np.float32(t)
+    V[0, 0, 1:] = (126 + off) * np.float32(t)
+    V[1, 0, 1:] = (-126 + off) * np.float32(t)
+    V[:, 0, d // 2:] = off * np.float32(t)              # half of the dims small: the largest |V|, not a typical one, sets the bound
+    scale = 1.0 / math.sqrt(d)
+    # D = scale * ||q||_1 * 1.001 * 127 s / 254  ->  the constant q value that gives D_target
+    qv = D_target / (scale * (d - 1) * 1.001 * float(s) / 2)
+    q = np.zeros((1, 1, d), dtype=np.float32)
+    q[0, 0, 1:] = np.float32(qv)
+    return q, K, V, scale
+
+
+@pytest.mark.parametrize("D_target", [0.01, 0.05, 0.3])
+def test_int8_error_bound_is_attained_from_below_and_never_exceeded(D_target):
+    """The bound is held from both sides: on rows that sit half a code step off, aligned with the query, the true
+    error reaches 90 % of it (a bound twice too large fails here), and it stays below it (a bound too small fails)."""
+    q, K, V, scale = int8_bound_worst_case(D_target)
+    codes, sc = oracle.kv_quantise_int8(K)
+    assert np.array_equal(codes[0], codes[1]) and sc[0, 0] == np.float32(2.0 ** -5)      # the construction holds
+    exact = oracle.cross_attn(q, K, V, 1, scale)
+    coded = oracle.cross_attn_int8(q, K, V, 1, scale)
+    err = np.abs(coded - exact).max()
+    bound = oracle.cross_attn_int8_error_bound(q, K, V, scale)
+    assert 0.90 * bound <= err <= bound, (err, bound, err / bound)
+    # closed form of this case: the coded rows tie (weights 1/2, 1/2), the exact weights are (1 +- tanh(delta/2))/2
+    delta = scale * float(q.astype(np.float64).sum()) * 0.998046875 * 2.0 ** -5
+    t = 2.0 ** -7
+    want = 0.4990234375 * t + math.tanh(0.5 * delta) * 126 * t
+    assert abs(err - want) <= 1e-9 * want, (err, want)
+
+
+def test_int8_error_bound_terms_scale_as_the_derivation_says():
+    """V-only case (q = 0: every weight is exact) leaves the half-step term alone; doubling every magnitude doubles
+    the bound's V term and leaves D-dependence to the K term."""
+    q, K, V, scale = int8_bound_worst_case(0.05)
+    q0 = np.zeros_like(q)
+    b0 = oracle.cross_attn_int8_error_bound(q0, K, V, scale)
+    assert abs(b0 - 1.001 * 127 * 2.0 ** -7 / 254) <= 1e-15
+    err0 = np.abs(oracle.cross_attn_int8(q0, K, V, 1, scale) - oracle.cross_attn(q0, K, V, 1, scale)).max()
+    assert 0.99 * b0 <= err0 <= b0
+    assert abs(oracle.cross_attn_int8_error_bound(q0, K, 2 * V, scale) - 2 * b0) <= 1e-15
+    # random rows stay inside it with room to spare (it is a worst case, not a typical one)
+    qr, kr, vr = ys.qkv(11, 64, 2, 1, 32, 1.0, "f32")
+    e = np.abs(oracle.cross_attn_int8(qr[-1:], kr, vr, 63, scale) - oracle.cross_attn(qr[-1:], kr, vr, 63, scale)).max()
+    assert 0 < e < 0.5 * oracle.cross_attn_int8_error_bound(qr[-1:], kr, vr, scale)
+
+
 def test_stack_with_8_bit_cache_keeps_the_generation_and_early_exit_invariants():
     """cache_bits = 8 changes K^, V^ to their coded values and nothing else: early exit still equals the last row of
     the full forward, token-by-token generation still equals the all-at-once forward (rows are coded one by one, each
