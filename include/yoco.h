@@ -188,6 +188,24 @@ int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const
                            float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * yoco_cross_attn_decode for callers that cannot allocate device memory or
+ * carry a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same operation, same kernels and bit-identical
+ * results; the split partials live in a static device array inside the library
+ * (YOCO_NOALLOC_SCRATCH_BYTES per GPU the library runs on, held until the
+ * process ends) instead of a caller workspace. The call allocates and frees
+ * nothing. A shape whose partials (yoco_cross_attn_decode_workspace) exceed the
+ * array is refused with YOCO_ERR_WORKSPACE before anything is launched.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time
+ * on one GPU (different streams or threads) race; calls on one stream are
+ * ordered. Nothing in the array needs clearing between calls (pass 1 writes
+ * every partial the merge reads).
+ */
+#define YOCO_NOALLOC_SCRATCH_BYTES ((size_t)4 << 20)
+int yoco_cross_attn_decode_noalloc(const yoco_kv_cache* c, const void* q, void* o, const int64_t* lens, int Hq,
+                                   float scale, void* stream);
+
+/*
  * ---- Token-by-token generation through the self-decoder ----
  * Sliding-window attention needs only the last C rows of a layer's K and V
  * (section 3.2, Eq. 8; the footnote of section 2.3 and Table 1 count this

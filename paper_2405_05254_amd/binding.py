@@ -43,6 +43,7 @@ def lib():
     L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp, sz, vp]
     L.yoco_cross_attn_decode_workspace.argtypes = [C.POINTER(_Cache), i32, C.POINTER(sz), C.POINTER(i32)]
     L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
+    L.yoco_cross_attn_decode_noalloc.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp]
     L.yoco_swa_cache_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
     L.yoco_kv_cache_append.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, i32, vp]
     L.yoco_swa_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, vp, vp, i32, f32, vp, sz, vp]
@@ -52,7 +53,7 @@ def lib():
     L.yoco_ceiling_mfma.argtypes = [vp, vp, i32, i32, vp]
     L.yoco_ceiling_stream_read.argtypes = [vp, sz, vp, i32, vp]
     for name in ("yoco_ceiling_mfma", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
-                 "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode",
+                 "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode", "yoco_cross_attn_decode_noalloc",
                  "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode",
                  "yoco_gret_prefill_workspace", "yoco_gret_prefill", "yoco_gret_decode"):
         getattr(L, name).restype = i32
@@ -199,6 +200,25 @@ def cross_attn_decode(cache, q, lens, scale, workspace, out=None):
     o = _out(out, q)
     _check(lib().yoco_cross_attn_decode(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq,
                                         scale, *_ws(workspace), _stream()))
+    return o
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def cross_attn_decode_noalloc(cache, q, lens, scale, out):
+    """yoco_cross_attn_decode_noalloc: the decode step with the library's static scratch instead of a workspace.
+    `out` is required (this wrapper allocates nothing either)."""
+    B, Hq, d = q.shape
+    if B != cache.B or d != cache.d or q.dtype != cache.io_dtype:
+        raise YocoError("q does not match the cache")
+    if lens.dtype != torch.int64 or lens.shape != (B,):
+        raise YocoError("lens must be int64 [B]")
+    if out is None:
+        raise YocoError("out is required")
+    o = _out(out, q)
+    _check(lib().yoco_cross_attn_decode_noalloc(C.byref(cache.desc), _dev(q, "q"), _dev(o, "o"), _dev(lens, "lens"), Hq,
+                                                scale, _stream()))
     return o
 
 

@@ -1,7 +1,10 @@
-// C ABI of libyoco: argument validation and dispatch. No device code here.
+// C ABI of libyoco: argument validation and dispatch. No kernels here; the one device object is the static scratch
+// array of yoco_cross_attn_decode_noalloc.
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
+
+#include <mutex>
 
 #include "yoco_common.h"
 
@@ -110,6 +113,34 @@ int check_gret_shape(int B, int64_t T, int H, int dk, int dv, int dtype) {
   if (!dtype_ok(dtype)) return fail(YOCO_ERR_UNSUPPORTED, "dtype %d", dtype);
   if (dk <= 0 || dv <= 0 || dk > 256 || dv > 256) return fail(YOCO_ERR_UNSUPPORTED, "head dims %d, %d not in [8, 256]", dk, dv);
   if (dk % 8 || dv % 8) return fail(YOCO_ERR_ALIGNMENT, "head dims %d, %d are not multiples of 8", dk, dv);
+  return YOCO_OK;
+}
+
+// ---- static scratch for callers that cannot allocate (yoco_cross_attn_decode_noalloc). Every GPU the library
+// runs on holds its own copy of the array, at its own address, until the process ends. In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and copies get the per-device address looked up below.
+constexpr size_t kScratchBytes = YOCO_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device with that device current.
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_result(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(YOCO_ERR_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_result(e, "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(YOCO_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
   return YOCO_OK;
 }
 
@@ -317,6 +348,27 @@ int yoco_cross_attn_decode(const yoco_kv_cache* c, const void* q, void* o, const
   if (rc) return rc;
   if (workspace_bytes < need) return fail(YOCO_ERR_WORKSPACE, "workspace %zu < %zu bytes", workspace_bytes, need);
   return run_decode(*c, q, o, lens, 0, Hq, scale, (float*)workspace, splits, (hipStream_t)stream, "cross_attn_decode");
+}
+
+int yoco_cross_attn_decode_noalloc(const yoco_kv_cache* c, const void* q, void* o, const int64_t* lens, int Hq, float scale,
+                                   void* stream) {
+  // Validate the shape and the size first: a call that is too large must fail before anything touches the device.
+  int rc = check_cache(c);
+  if (rc) return rc;
+  if (!q || !o || !lens) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  size_t need = 0;
+  int splits = 0;
+  rc = yoco_cross_attn_decode_workspace(c, Hq, &need, &splits);
+  if (rc) return rc;
+  if (need > kScratchBytes)
+    return fail(YOCO_ERR_WORKSPACE, "cross_attn_decode_noalloc: the partial results need %zu bytes, the static scratch holds %zu",
+                need, kScratchBytes);
+  void* ptr = nullptr;
+  rc = scratch_of_current_device(&ptr);
+  if (rc) return rc;
+  // Every partial the merge reads is written by pass 1 of the same call (empty splits included), so nothing in the
+  // array has to be cleared between calls.
+  return yoco_cross_attn_decode(c, q, o, lens, Hq, scale, ptr, kScratchBytes, stream);
 }
 
 int yoco_swa_decode(const yoco_kv_cache* ring, const void* q, const void* k_new, const void* v_new, void* o,

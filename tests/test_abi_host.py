@@ -96,6 +96,15 @@ def test_calls_validate_before_launching():
     assert L.yoco_cross_attn_decode(C.byref(d), p, p, p, 4, 1.0, p, n.value - 1, None) == -4
     assert L.yoco_cross_attn_decode(C.byref(d), p, p, None, 4, 1.0, p, n.value, None) == -1
     assert b"null" in L.yoco_last_error_string()
+    # the variant with the static scratch: arguments and size are refused on the host, before any device call
+    assert L.yoco_cross_attn_decode_noalloc(C.byref(d), p, p, None, 4, 1.0, None) == -1
+    assert L.yoco_cross_attn_decode_noalloc(None, p, p, p, 4, 1.0, None) == -1
+    big = yb._Cache()
+    big.k, big.v, big.B, big.Hkv, big.d, big.dtype, big.N_cap = p, p, 64, 8, 256, yoco.BF16, 100
+    assert L.yoco_cross_attn_decode_workspace(C.byref(big), 64, C.byref(n), C.byref(s)) == 0
+    assert n.value > yoco.NOALLOC_SCRATCH_BYTES
+    assert L.yoco_cross_attn_decode_noalloc(C.byref(big), p, p, p, 64, 1.0, None) == -4
+    assert b"static scratch" in L.yoco_last_error_string()
 
 
 def test_decode_splits_fill_the_chip():
