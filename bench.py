@@ -24,10 +24,24 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2516.6    # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
-# HBM bytes of one SWA prefill launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) of `bench.py --only swa`, each scaled by what the counter reads for a 1 GiB copy (`--only calib`:
-# FETCH_SIZE reads 0.5 GiB -> factor 2.0, WRITE_SIZE reads 1.0 GiB -> factor 1.0). See profiles/.
-SWA_TRAFFIC_BYTES = {"fetch": 2.0 * 308514.2 * 1024, "write": 1.0 * 198132.5 * 1024}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "hbm_traffic_swa_prefill_32k_and_decode.md")
+
+
+def swa_traffic_from_profile():
+    """HBM bytes of one SWA prefill launch at the headline shape, read at run time from the committed rocprofv3
+    summary (two --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy; the
+    file gives commands and factors). Returns (fetch_bytes, write_bytes) or None when the file or its rows are missing:
+    the line then carries traffic = null rather than a stale constant."""
+    try:
+        got = {}
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) > 6 and cells[1].startswith("swa_mfma_kernel") and cells[2] in ("FETCH_SIZE", "WRITE_SIZE"):
+                    got[cells[2]] = float(cells[5])          # the "scaled bytes" column
+        return (got["FETCH_SIZE"], got["WRITE_SIZE"])
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def swa_flops(T, H, d, C):
@@ -163,9 +177,13 @@ def main():
         ceilings = dict(
             mfma_bf16_TFLOPs_random_operands=round(rate(lambda: yoco.ceiling_mfma(seed_rand, sink, 20000, 256), 3) / 1e12, 1),
             mfma_bf16_TFLOPs_zero_operands=round(rate(lambda: yoco.ceiling_mfma(seed_zero, sink, 20000, 256), 3) / 1e12, 1),
+            attn_loop_lds_fed_TFLOPs=round(rate(lambda: yoco.ceiling_attn_loop(seed_rand, sink, 4000, 256, 1), 3) / 1e12, 1),
+            attn_loop_lds_fed_with_softmax_TFLOPs=round(rate(lambda: yoco.ceiling_attn_loop(seed_rand, sink, 4000, 256, 2), 3) / 1e12, 1),
             stream_read_GBps=round(max(rate(lambda n=n: yoco.ceiling_stream_read(big, sink, n), 10) for n in (256, 512, 1024)) / 1e9, 1),
-            note="MFMA-only loop (2 wavefronts per SIMD, register operands) and a 2 GiB streaming read with 128-bit "
-                 "nontemporal loads (best of 1, 2 and 4 workgroups per CU)")
+            note="MFMA-only loop (2 wavefronts per SIMD, register operands); the attention inner loop on its own with random "
+                 "operands (every MFMA's A operand a fresh LDS fragment; then with the softmax work of 32 scores per lane and 32 "
+                 "MFMAs interleaved): no staging, masks, barriers or tile walk, i.e. what the prefill kernel could reach at best; "
+                 "and a 2 GiB streaming read with 128-bit nontemporal loads (best of 1, 2 and 4 workgroups per CU)")
         del big
         torch.cuda.empty_cache()
 
@@ -346,6 +364,7 @@ def main():
                    sample="%d sampled (row, head) outputs of the same T=32768 x 24-head SWA workload in %.1f s; "
                           "a token = 24 head rows" % (n, dt))
 
+    traffic = swa_traffic_from_profile()
     out = {
         "metric": "swa_prefill_tokens_per_s", "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -359,8 +378,10 @@ def main():
         "peaks": {"mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "hbm_GBps": HBM_PEAK_GBS, "measured": ceilings},
         "roofline": {"kernel": "yoco_swa_prefill", "bound": "mfma", "achieved": round(swa_tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(swa_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": int(SWA_TRAFFIC_BYTES["fetch"] + SWA_TRAFFIC_BYTES["write"]),
-                     "traffic_note": "HBM bytes per launch (fetch 0.632 GB + write 0.203 GB) against 0.805 GB algorithmic"},
+                     "traffic": None if traffic is None else int(traffic[0] + traffic[1]),
+                     "traffic_note": "not measured in this run" if traffic is None else
+                     "HBM bytes per launch read from profiles/%s (rocprofv3 --pmc FETCH_SIZE %.3f GB + WRITE_SIZE %.3f GB, "
+                     "scaled by a 1 GiB copy) against 0.805 GB algorithmic" % (os.path.basename(TRAFFIC_PROFILE), traffic[0] / 1e9, traffic[1] / 1e9)},
         "decode": decode,
         "gated_retention": gret,
         "e2e_early_exit_128k": e2e,

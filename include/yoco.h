@@ -310,8 +310,16 @@ int yoco_gret_decode(const void* q, const void* k, const void* v, const float* l
  * workgroups * 8 * 8 * iters * 32768. `sink`: 4 device bytes, practically never
  * written. yoco_ceiling_stream_read: reads `bytes` (a multiple of 16) of `buf`
  * once with 128-bit nontemporal loads, `workgroups` contiguous shares.
+ * yoco_ceiling_attn_loop: the inner loop of flash attention on its own (no
+ * staging, masks, barriers or tile walk), same operands, `workgroups`
+ * workgroups of 8 wavefronts, 32 * iters MFMAs per wavefront. mode 1: every
+ * MFMA takes its A operand as a fresh 128-bit LDS fragment; mode 2: the same
+ * plus the softmax work of two scores (2 fma, 2 exp2, fp16 pack, row-sum dot2)
+ * after every second MFMA, the ratio of the prefill kernel at head_dim 128.
+ * flops per launch = workgroups * 8 * 32 * iters * 32768.
  */
 int yoco_ceiling_mfma(const void* seed, void* sink, int iters, int workgroups, void* stream);
+int yoco_ceiling_attn_loop(const void* seed, void* sink, int iters, int workgroups, int mode, void* stream);
 int yoco_ceiling_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). */

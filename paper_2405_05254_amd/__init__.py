@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     kv_cache_bytes, swa_prefill, global_kv_write, cross_attn_prefill,
     cross_attn_decode, cross_attn_decode_workspace, cross_attn_decode_noalloc, NOALLOC_SCRATCH_BYTES, version,
     swa_cache_write, kv_cache_append, swa_decode,
-    gret_prefill_workspace, gret_prefill, gret_decode, ceiling_mfma, ceiling_stream_read,
+    gret_prefill_workspace, gret_prefill, gret_decode, ceiling_mfma, ceiling_attn_loop, ceiling_stream_read,
 )

@@ -51,8 +51,9 @@ def lib():
     L.yoco_gret_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, f32, i32, f32, i32, vp, sz, vp]
     L.yoco_gret_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, i32, f32, i32, vp]
     L.yoco_ceiling_mfma.argtypes = [vp, vp, i32, i32, vp]
+    L.yoco_ceiling_attn_loop.argtypes = [vp, vp, i32, i32, i32, vp]
     L.yoco_ceiling_stream_read.argtypes = [vp, sz, vp, i32, vp]
-    for name in ("yoco_ceiling_mfma", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
+    for name in ("yoco_ceiling_mfma", "yoco_ceiling_attn_loop", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
                  "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode", "yoco_cross_attn_decode_noalloc",
                  "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode",
                  "yoco_gret_prefill_workspace", "yoco_gret_prefill", "yoco_gret_decode"):
@@ -323,6 +324,13 @@ def ceiling_mfma(seed, sink, iters, workgroups):
     """Launch the MFMA-only loop (yoco_ceiling_mfma); returns the flops of the launch."""
     _check(lib().yoco_ceiling_mfma(_dev(seed, "seed"), _dev(sink, "sink"), iters, workgroups, _stream()))
     return workgroups * 8 * 8 * iters * 32768.0
+
+
+def ceiling_attn_loop(seed, sink, iters, workgroups, mode):
+    """Launch the attention inner loop on its own (yoco_ceiling_attn_loop; mode 1: LDS-fed products, 2: with the
+    softmax work); returns the flops of the launch."""
+    _check(lib().yoco_ceiling_attn_loop(_dev(seed, "seed"), _dev(sink, "sink"), iters, workgroups, mode, _stream()))
+    return workgroups * 8 * 32 * iters * 32768.0
 
 
 def ceiling_stream_read(buf, sink, workgroups):

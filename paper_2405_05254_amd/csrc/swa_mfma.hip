@@ -38,10 +38,7 @@ namespace {
 constexpr int kD = 128;          // head dimension
 constexpr int kBN = 64;          // keys per tile
 constexpr int kNQ = 32;          // query rows per wavefront
-#ifndef YOCO_SWA_WAVES
-#define YOCO_SWA_WAVES 4
-#endif
-constexpr int kWaves = YOCO_SWA_WAVES;
+constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kStageRows = 1024 / kThreads;   // 16-byte chunks of a K (or V) tile per thread
 constexpr int kStageStep = kThreads / 16;     // rows between a thread's chunks

@@ -463,6 +463,14 @@ int yoco_ceiling_mfma(const void* seed, void* sink, int iters, int workgroups, v
   return hip_result(yoco::launch_mfma_ceiling(seed, sink, iters, workgroups, (hipStream_t)stream), "ceiling_mfma");
 }
 
+int yoco_ceiling_attn_loop(const void* seed, void* sink, int iters, int workgroups, int mode, void* stream) {
+  if (!seed || !sink) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
+  if (!aligned16(seed)) return fail(YOCO_ERR_ALIGNMENT, "seed not 16-byte aligned");
+  if (iters <= 0 || workgroups <= 0) return fail(YOCO_ERR_INVALID_ARG, "non-positive iters or workgroups");
+  if (mode != 1 && mode != 2) return fail(YOCO_ERR_INVALID_ARG, "mode %d is neither 1 (LDS-fed products) nor 2 (with the softmax work)", mode);
+  return hip_result(yoco::launch_attn_loop_ceiling(seed, sink, iters, workgroups, mode, (hipStream_t)stream), "ceiling_attn_loop");
+}
+
 int yoco_ceiling_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, void* stream) {
   if (!buf || !sink) return fail(YOCO_ERR_INVALID_ARG, "null pointer");
   if (!aligned16(buf) || bytes % 16) return fail(YOCO_ERR_ALIGNMENT, "buffer not 16-byte aligned or size not a multiple of 16");

@@ -113,6 +113,7 @@ hipError_t launch_decode_i8(const yoco_kv_cache& c, const void* q, const int64_t
 
 // Measured-ceiling microbenchmarks (ceilings.hip).
 hipError_t launch_mfma_ceiling(const void* seed, void* sink, int iters, int workgroups, hipStream_t s);
+hipError_t launch_attn_loop_ceiling(const void* seed, void* sink, int iters, int workgroups, int mode, hipStream_t s);
 hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t s);
 
 // Partial result of one split, per (b, h, split): o[0..d), then the running max
