@@ -340,9 +340,24 @@ def main():
             es = ec["stack"]
             eq = ys.device_normal((1, ec["T"], es["Hq"], es["d"]), 700, 0.5, torch.bfloat16, dev)
             swa_layer_ms = timed(lambda: yoco.swa_prefill(eq, eq, eq, es["window"], scale))
-            del st, tok, eq
+            # Eq. 2 on all T rows (norm, two projections, cache write), as the stack does it and with the norm folded
+            # into the write call (yoco_global_kv_write_scaled)
+            xm = ys.device_normal((ec["T"], es["d_model"]), 701, 1.0, torch.bfloat16, dev)
+            kvc = yoco.KVCache(1, st.Hkv, st.d, ec["T"], torch.bfloat16, dev)
+
+            def best(fn, reps=5):
+                return min(timed(fn) for _ in range(reps))
+
+            eq2_plain_ms = best(lambda: st.write_cache(xm, kvc))
+            st.fused_kv_norm = True
+            st.kv["gW_K"] = (st.kv["ln"].float()[:, None] * st.kv["W_K"].float()).to(torch.bfloat16)
+            st.kv["gW_V"] = (st.kv["ln"].float()[:, None] * st.kv["W_V"].float()).to(torch.bfloat16)
+            eq2_folded_ms = best(lambda: st.write_cache(xm, kvc))
+            del st, tok, eq, xm, kvc
             torch.cuda.empty_cache()
         e2e = dict(T=ec["T"], early_exit_prefill_ms=round(ee_ms, 1), full_forward_ms=round(full_ms, 1),
+                   eq2_all_rows_ms=dict(norm_then_projections_then_write=round(eq2_plain_ms, 3),
+                                        norm_folded_into_the_write=round(eq2_folded_ms, 3)),
                    early_exit_speedup=round(full_ms / ee_ms, 2), early_exit_tokens_per_s=round(ec["T"] / (ee_ms * 1e-3), 1),
                    swa_ms_per_layer=round(swa_layer_ms, 2),
                    swa_share_of_early_exit_prefill=round(es["n_self"] * swa_layer_ms / ee_ms, 3),

@@ -150,6 +150,20 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
                          int64_t n, int src_dtype, void* stream);
 
 /*
+ * The same write with the RMSNorm of Eq. 2 folded in (section 2.2, Eq. 2 with
+ * LN = RMSNorm, section 2.1): since RMSNorm(x) W = (1 / rms(x)) * (x (diag(g) W)),
+ * the caller can skip the normalisation pass over X^{L/2}, multiply the raw
+ * rows by the gain-scaled weights diag(g) W_K, diag(g) W_V, and hand over those
+ * products together with one float32 factor per row, row_scale[r] =
+ * 1 / sqrt(mean(x_r^2) + eps) (device memory, [n]). Every element is multiplied
+ * by its row's factor in float32 and then cast (or coded, for an 8-bit cache)
+ * exactly as yoco_global_kv_write does. row_scale == NULL is
+ * yoco_global_kv_write.
+ */
+int yoco_global_kv_write_scaled(const yoco_kv_cache* c, const void* k, const void* v, const float* row_scale,
+                                int b, int64_t pos0, int64_t n, int src_dtype, void* stream);
+
+/*
  * Cross-decoder attention of Eq. 3 for Tq query rows of sequence b; row i has
  * absolute position q_pos0 + i and attends to cache rows j <= q_pos0 + i
  * (causal). q, o: [Tq,Hq,d] of the cache dtype (bf16 for an 8-bit cache).

@@ -94,6 +94,20 @@ def global_kv(X, gain, W_K, W_V, Hkv, eps=1e-6):
     return Kh.reshape(T, Hkv, -1), Vh.reshape(T, Hkv, -1)
 
 
+def global_kv_scaled_form(X, gain, W_K, W_V, Hkv, eps=1e-6):
+    """Eq. 2 with the RMSNorm moved behind the projections (section 2.2, Eq. 2; section 2.1: LN = RMSNorm).
+    RMSNorm(x) W = (x / rms(x) * g) W = (1 / rms(x)) * (x (diag(g) W)), so the un-normalised rows times the
+    gain-scaled weights, and one factor per row, carry the same cache. Returns (K_raw, V_raw [T,Hkv,d],
+    row_scale [T]) with K^ = K_raw * row_scale[:, None, None]."""
+    X = np.asarray(X, dtype=F64)
+    g = np.asarray(gain, dtype=F64)
+    row_scale = 1.0 / np.sqrt((X * X).mean(axis=-1) + eps)
+    Kraw = X @ (g[:, None] * np.asarray(W_K, dtype=F64))
+    Vraw = X @ (g[:, None] * np.asarray(W_V, dtype=F64))
+    T = X.shape[0]
+    return Kraw.reshape(T, Hkv, -1), Vraw.reshape(T, Hkv, -1), row_scale
+
+
 def cross_attn_row(Q, Khat, Vhat, i, h, q_pos0, scale):
     """Row i, head h of the cross-decoder's attention (section 2.2, Eq. 3):
     standard causal attention of the query at absolute position q_pos0 + i

@@ -40,6 +40,7 @@ def lib():
     L.yoco_kv_cache_init.argtypes = [vp, sz, i32, i32, i32, i64, i32, C.POINTER(_Cache)]
     L.yoco_swa_prefill.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i64, f32, i32, vp]
     L.yoco_global_kv_write.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, vp]
+    L.yoco_global_kv_write_scaled.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, i64, i64, i32, vp]
     L.yoco_cross_attn_prefill.argtypes = [C.POINTER(_Cache), vp, vp, i32, i64, i64, i32, f32, vp, sz, vp]
     L.yoco_cross_attn_decode_workspace.argtypes = [C.POINTER(_Cache), i32, C.POINTER(sz), C.POINTER(i32)]
     L.yoco_cross_attn_decode.argtypes = [C.POINTER(_Cache), vp, vp, vp, i32, f32, vp, sz, vp]
@@ -53,7 +54,7 @@ def lib():
     L.yoco_ceiling_mfma.argtypes = [vp, vp, i32, i32, vp]
     L.yoco_ceiling_attn_loop.argtypes = [vp, vp, i32, i32, i32, vp]
     L.yoco_ceiling_stream_read.argtypes = [vp, sz, vp, i32, vp]
-    for name in ("yoco_ceiling_mfma", "yoco_ceiling_attn_loop", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write",
+    for name in ("yoco_ceiling_mfma", "yoco_ceiling_attn_loop", "yoco_ceiling_stream_read", "yoco_kv_cache_bytes", "yoco_kv_cache_init", "yoco_swa_prefill", "yoco_global_kv_write", "yoco_global_kv_write_scaled",
                  "yoco_cross_attn_prefill", "yoco_cross_attn_decode_workspace", "yoco_cross_attn_decode", "yoco_cross_attn_decode_noalloc",
                  "yoco_swa_cache_write", "yoco_kv_cache_append", "yoco_swa_decode",
                  "yoco_gret_prefill_workspace", "yoco_gret_prefill", "yoco_gret_decode"):
@@ -170,6 +171,18 @@ def global_kv_write(cache, k, v, b, pos0):
         raise YocoError("k/v rows do not match the cache")
     _check(lib().yoco_global_kv_write(C.byref(cache.desc), _dev(k, "k") if n else None, _dev(v, "v") if n else None,
                                       b, pos0, n, _dtype(k), _stream()))
+
+
+def global_kv_write_scaled(cache, k, v, row_scale, b, pos0):
+    """k, v [n,Hkv,d] un-normalised projections x (diag(g) W), row_scale float32 [n] = 1/rms(x): rows are scaled in
+    float32 and stored like global_kv_write (yoco_global_kv_write_scaled)."""
+    n = k.shape[0]
+    if n and (k.shape != (n, cache.Hkv, cache.d) or v.shape != k.shape or v.dtype != k.dtype):
+        raise YocoError("k/v rows do not match the cache")
+    if row_scale.dtype != torch.float32 or row_scale.shape != (n,):
+        raise YocoError("row_scale must be float32 [n]")
+    _check(lib().yoco_global_kv_write_scaled(C.byref(cache.desc), _dev(k, "k") if n else None, _dev(v, "v") if n else None,
+                                             _dev(row_scale, "row_scale") if n else None, b, pos0, n, _dtype(k), _stream()))
 
 
 def cross_attn_prefill(cache, q, b, q_pos0, scale, out=None, workspace=None):

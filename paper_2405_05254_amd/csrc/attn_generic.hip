@@ -257,8 +257,8 @@ __device__ __forceinline__ void store8(bf16_t* p, const Row8<float>& r) {
 // (whose caller passes r0 = max(0, n - N_cap), so no two rows share a slot).
 template <typename S, typename D>
 __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S* __restrict__ k,
-                                                       const S* __restrict__ v, int b, int64_t pos0, int64_t r0,
-                                                       int64_t n) {
+                                                       const S* __restrict__ v, const float* __restrict__ row_scale, int b,
+                                                       int64_t pos0, int64_t r0, int64_t n) {
   const int d8 = c.d / 8;
   const int64_t total = (n - r0) * c.Hkv * d8;           // groups of 8 elements
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -273,8 +273,22 @@ __global__ void __launch_bounds__(256) kv_write_kernel(yoco_kv_cache c, const S*
     Row8<S> kr, vr;
     kr.load(k + src);
     vr.load(v + src);
-    store8((D*)c.k + dst, kr);
-    store8((D*)c.v + dst, vr);
+    if (row_scale) {                                       // Eq. 2 with the norm's 1/rms applied after the projections
+      const float rs = row_scale[r];
+      Row8<float> ks, vs;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ks.lo[i] = kr.get(i) * rs;
+        ks.hi[i] = kr.get(4 + i) * rs;
+        vs.lo[i] = vr.get(i) * rs;
+        vs.hi[i] = vr.get(4 + i) * rs;
+      }
+      store8((D*)c.k + dst, ks);
+      store8((D*)c.v + dst, vs);
+    } else {
+      store8((D*)c.k + dst, kr);
+      store8((D*)c.v + dst, vr);
+    }
   }
 }
 
@@ -308,20 +322,20 @@ __global__ void __launch_bounds__(256) kv_append_kernel(yoco_kv_cache c, const S
   }
 }
 
-hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t r0,
+hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, const float* row_scale, int b, int64_t pos0, int64_t r0,
                            int64_t n, int src_dtype, hipStream_t s) {
   const int64_t total = (n - r0) * c.Hkv * (c.d / 8);
   int64_t blocks = (total + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   dim3 grid((unsigned)blocks), block(256);
   if (src_dtype == YOCO_F32 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_write_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, r0, n);
+    hipLaunchKernelGGL((kv_write_kernel<float, float>), grid, block, 0, s, c, (const float*)k, (const float*)v, row_scale, b, pos0, r0, n);
   else if (src_dtype == YOCO_F32 && c.dtype == YOCO_BF16)
-    hipLaunchKernelGGL((kv_write_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, b, pos0, r0, n);
+    hipLaunchKernelGGL((kv_write_kernel<float, bf16_t>), grid, block, 0, s, c, (const float*)k, (const float*)v, row_scale, b, pos0, r0, n);
   else if (src_dtype == YOCO_BF16 && c.dtype == YOCO_F32)
-    hipLaunchKernelGGL((kv_write_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, r0, n);
+    hipLaunchKernelGGL((kv_write_kernel<bf16_t, float>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, row_scale, b, pos0, r0, n);
   else
-    hipLaunchKernelGGL((kv_write_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, b, pos0, r0, n);
+    hipLaunchKernelGGL((kv_write_kernel<bf16_t, bf16_t>), grid, block, 0, s, c, (const bf16_t*)k, (const bf16_t*)v, row_scale, b, pos0, r0, n);
   return hipGetLastError();
 }
 

@@ -41,7 +41,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // pos != null: one row per sequence ([B,Hkv,128]) goes to slot pos[b], skipped when outside [0, N_cap).
 template <typename S>
 __global__ void __launch_bounds__(256) kv_code_i8_kernel(yoco_kv_cache c, const S* __restrict__ k, const S* __restrict__ v,
-                                                         int b_fixed, int64_t pos0, int64_t n, const int64_t* __restrict__ pos) {
+                                                         const float* __restrict__ row_scale, int b_fixed, int64_t pos0, int64_t n,
+                                                         const int64_t* __restrict__ pos) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (wave >= n * c.Hkv * 2) return;                       // uniform over the wavefront
@@ -56,7 +57,8 @@ __global__ void __launch_bounds__(256) kv_code_i8_kernel(yoco_kv_cache c, const 
     if (slot < 0 || slot >= c.N_cap) return;
   }
   const S* src = (which ? v : k) + (row * c.Hkv + g) * kD + lane * 2;
-  const float x0 = Elem<S>::load(src), x1 = Elem<S>::load(src + 1);
+  const float rs = row_scale ? row_scale[row] : 1.f;       // the row as it is cached: float32(x * rs), then the coding rule
+  const float x0 = Elem<S>::load(src) * rs, x1 = Elem<S>::load(src + 1) * rs;
   float a = fmaxf(fabsf(x0), fabsf(x1));
 #pragma unroll
   for (int off = 32; off; off >>= 1) a = fmaxf(a, __shfl_xor(a, off));
@@ -105,13 +107,18 @@ template <> struct Row32<bf16_t> {
 
 template <typename S>
 __global__ void __launch_bounds__(256) kv_code_i8_block_kernel(yoco_kv_cache c, const S* __restrict__ k, const S* __restrict__ v,
-                                                               int b, int64_t blk0) {
+                                                               const float* __restrict__ row_scale, int b, int64_t blk0) {
   __shared__ __attribute__((aligned(16))) unsigned char tile[kI8ScaleOffset];
   const int t = threadIdx.x, rho = t >> 2, part = t & 3;
   const int g = blockIdx.y, which = blockIdx.z;
   const S* src = (which ? v : k) + (((int64_t)blockIdx.x * 64 + rho) * c.Hkv + g) * kD + part * 32;
   float x[32];
   Row32<S>::load(src, x);
+  if (row_scale) {
+    const float rs = row_scale[(int64_t)blockIdx.x * 64 + rho];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] *= rs;
+  }
   float a = 0.f;
 #pragma unroll
   for (int i = 0; i < 32; ++i) a = fmaxf(a, fabsf(x[i]));
@@ -401,18 +408,19 @@ bool decode_i8_supported(const yoco_kv_cache& c, int Hq) {
   return G >= 1 && G <= 16 && c.Hkv <= 65535;
 }
 
-hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
-                             const int64_t* pos, int src_dtype, hipStream_t s) {
+hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, const float* row_scale, int b, int64_t pos0,
+                             int64_t n, const int64_t* pos, int src_dtype, hipStream_t s) {
   // rows [r0, r1) of the source, one wavefront per (row, head, plane)
   auto by_rows = [&](int64_t r0, int64_t r1, int64_t slot0) {
     if (r1 <= r0) return;
     const int64_t waves = (r1 - r0) * c.Hkv * 2;
     const size_t skip = (size_t)r0 * c.Hkv * kD;
     dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+    const float* rs = row_scale ? row_scale + r0 : nullptr;
     if (src_dtype == YOCO_F32)
-      hipLaunchKernelGGL(kv_code_i8_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, b, slot0, r1 - r0, pos);
+      hipLaunchKernelGGL(kv_code_i8_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, rs, b, slot0, r1 - r0, pos);
     else
-      hipLaunchKernelGGL(kv_code_i8_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, b, slot0, r1 - r0, pos);
+      hipLaunchKernelGGL(kv_code_i8_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, rs, b, slot0, r1 - r0, pos);
   };
   if (pos) {                                  // one row per sequence at device-side positions
     by_rows(0, c.B, 0);
@@ -429,10 +437,11 @@ hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* 
   {
     const size_t skip = (size_t)(first_full - pos0) * c.Hkv * kD;
     dim3 grid((unsigned)((last_full - first_full) / 64), c.Hkv, 2), block(256);
+    const float* rs = row_scale ? row_scale + (first_full - pos0) : nullptr;
     if (src_dtype == YOCO_F32)
-      hipLaunchKernelGGL(kv_code_i8_block_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, b, first_full / 64);
+      hipLaunchKernelGGL(kv_code_i8_block_kernel<float>, grid, block, 0, s, c, (const float*)k + skip, (const float*)v + skip, rs, b, first_full / 64);
     else
-      hipLaunchKernelGGL(kv_code_i8_block_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, b, first_full / 64);
+      hipLaunchKernelGGL(kv_code_i8_block_kernel<bf16_t>, grid, block, 0, s, c, (const bf16_t*)k + skip, (const bf16_t*)v + skip, rs, b, first_full / 64);
   }
   by_rows(last_full - pos0, n, last_full);
   return hipGetLastError();

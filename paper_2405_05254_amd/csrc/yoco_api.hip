@@ -214,8 +214,8 @@ int yoco_swa_prefill(const void* q, const void* k, const void* v, void* o, int B
   return hip_result(yoco::launch_attn_generic(a, dtype, (hipStream_t)stream), "swa_prefill");
 }
 
-int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
-                         int src_dtype, void* stream) {
+int yoco_global_kv_write_scaled(const yoco_kv_cache* c, const void* k, const void* v, const float* row_scale, int b, int64_t pos0,
+                                int64_t n, int src_dtype, void* stream) {
   int rc = check_cache(c);
   if (rc) return rc;
   if (n < 0) return fail(YOCO_ERR_INVALID_ARG, "negative row count");
@@ -227,12 +227,18 @@ int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, i
   if (n == 0) return YOCO_OK;
   if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
+  if (row_scale && (((uintptr_t)row_scale) & 3u)) return fail(YOCO_ERR_ALIGNMENT, "row_scale is not 4-byte aligned");
   if (c->dtype == YOCO_INT8) {
     if (n * c->Hkv > (int64_t)1 << 32) return fail(YOCO_ERR_UNSUPPORTED, "too many rows for one call");
     if (c->Hkv > 65535) return fail(YOCO_ERR_UNSUPPORTED, "Hkv %d exceeds the grid limit", c->Hkv);
-    return hip_result(yoco::launch_kv_code_i8(*c, k, v, b, pos0, n, nullptr, src_dtype, (hipStream_t)stream), "global_kv_write");
+    return hip_result(yoco::launch_kv_code_i8(*c, k, v, row_scale, b, pos0, n, nullptr, src_dtype, (hipStream_t)stream), "global_kv_write");
   }
-  return hip_result(yoco::launch_kv_write(*c, k, v, b, pos0, 0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
+  return hip_result(yoco::launch_kv_write(*c, k, v, row_scale, b, pos0, 0, n, src_dtype, (hipStream_t)stream), "global_kv_write");
+}
+
+int yoco_global_kv_write(const yoco_kv_cache* c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+                         int src_dtype, void* stream) {
+  return yoco_global_kv_write_scaled(c, k, v, nullptr, b, pos0, n, src_dtype, stream);
 }
 
 int yoco_swa_cache_write(const yoco_kv_cache* ring, const void* k, const void* v, int b, int64_t pos0, int64_t n,
@@ -249,7 +255,7 @@ int yoco_swa_cache_write(const yoco_kv_cache* ring, const void* k, const void* v
   if (!k || !v) return fail(YOCO_ERR_INVALID_ARG, "null row pointer");
   if (!aligned16(k) || !aligned16(v)) return fail(YOCO_ERR_ALIGNMENT, "row pointer not 16-byte aligned");
   const int64_t r0 = n > ring->N_cap ? n - ring->N_cap : 0;     // earlier rows would be overwritten by later ones
-  return hip_result(yoco::launch_kv_write(*ring, k, v, b, pos0, r0, n, src_dtype, (hipStream_t)stream), "swa_cache_write");
+  return hip_result(yoco::launch_kv_write(*ring, k, v, nullptr, b, pos0, r0, n, src_dtype, (hipStream_t)stream), "swa_cache_write");
 }
 
 int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, const int64_t* pos, int ring,
@@ -262,7 +268,7 @@ int yoco_kv_cache_append(const yoco_kv_cache* c, const void* k, const void* v, c
   if (((uintptr_t)pos) & 7u) return fail(YOCO_ERR_ALIGNMENT, "pos is not 8-byte aligned");
   if (c->dtype == YOCO_INT8) {
     if (ring) return fail(YOCO_ERR_UNSUPPORTED, "a rolling window cache cannot be 8-bit");
-    return hip_result(yoco::launch_kv_code_i8(*c, k, v, 0, 0, c->B, pos, src_dtype, (hipStream_t)stream), "kv_cache_append");
+    return hip_result(yoco::launch_kv_code_i8(*c, k, v, nullptr, 0, 0, c->B, pos, src_dtype, (hipStream_t)stream), "kv_cache_append");
   }
   return hip_result(yoco::launch_kv_append(*c, k, v, pos, 0, ring, src_dtype, (hipStream_t)stream), "kv_cache_append");
 }

@@ -68,7 +68,7 @@ hipError_t launch_decode_generic(const yoco_kv_cache& c, const void* q, const in
                                  float scale, float* ws, int splits, hipStream_t s);
 hipError_t launch_decode_merge(const float* ws, void* o, int B, int Hq, int d, int splits, int dtype,
                                hipStream_t s);
-hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t r0,
+hipError_t launch_kv_write(const yoco_kv_cache& c, const void* k, const void* v, const float* row_scale, int b, int64_t pos0, int64_t r0,
                            int64_t n, int src_dtype, hipStream_t s);
 hipError_t launch_kv_append(const yoco_kv_cache& c, const void* k, const void* v, const int64_t* pos, int64_t bias, int ring,
                             int src_dtype, hipStream_t s);   // slot = pos[b] + bias
@@ -106,7 +106,8 @@ __host__ __device__ inline int i8_v_offset(int rho, int e) {      // V plane: by
 bool cache_i8_supported(int d);
 bool decode_i8_supported(const yoco_kv_cache& c, int Hq);
 // pos == null: rows [n,Hkv,128] of sequence b to slots pos0 ..; pos != null: one row per sequence to slot pos[b].
-hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, int b, int64_t pos0, int64_t n,
+// row_scale (or null): float32 [n], every source row is multiplied by its entry (in float32) before it is coded.
+hipError_t launch_kv_code_i8(const yoco_kv_cache& c, const void* k, const void* v, const float* row_scale, int b, int64_t pos0, int64_t n,
                              const int64_t* pos, int src_dtype, hipStream_t s);
 hipError_t launch_decode_i8(const yoco_kv_cache& c, const void* q, const int64_t* lens, int64_t fixed_len, int Hq, float scale,
                             float* ws, int splits, void* o_direct, hipStream_t s);   // q, o bf16

@@ -36,9 +36,10 @@ class YocoStack:
     """weights: the dict produced by the synthetic generator (numpy arrays);
     dtype: torch.float32 or torch.bfloat16."""
 
-    def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32, cache_dtype=None):
+    def __init__(self, weights, dtype, device="cuda", glue_dtype=torch.float32, cache_dtype=None, fused_kv_norm=False):
         self.dtype, self.device, self.glue = dtype, device, glue_dtype
         self.cache_dtype = dtype if cache_dtype is None else cache_dtype   # torch.int8: the global cache holds 8-bit codes
+        self.fused_kv_norm = fused_kv_norm   # Eq. 2 with the norm's 1/rms folded into the cache write (yoco_global_kv_write_scaled)
         self.capture = None          # dict layer-name -> (q, k, v, o) (gated retention: + log-decays, gate) when set by a test
 
         def dev(a):
@@ -55,6 +56,9 @@ class YocoStack:
         self.embed = dev(w["embed"])
         self.self_layers = [layer(L) for L in w["self"]]
         self.kv = layer(w["kv"])
+        if fused_kv_norm:             # gain-scaled weights diag(g) W_K, diag(g) W_V, formed once
+            self.kv["gW_K"] = (self.kv["ln"].float()[:, None] * self.kv["W_K"].float()).to(glue_dtype)
+            self.kv["gW_V"] = (self.kv["ln"].float()[:, None] * self.kv["W_V"].float()).to(glue_dtype)
         self.cross_layers = [layer(L) for L in w["cross"]]
         self.final_ln, self.W_out = dev(w["final_ln"]), dev(w["W_out"])
 
@@ -100,11 +104,18 @@ class YocoStack:
     # -- Eq. 2: the global cache, written once
     def write_cache(self, X, cache=None, pos0=0):
         T = X.shape[0]
+        if cache is None:
+            cache = yb.KVCache(1, self.Hkv, self.d, T, self.cache_dtype, self.device)
+        if self.fused_kv_norm:
+            # RMSNorm(x) W = (1 / rms(x)) (x (diag(g) W)): no normalised copy of X, the factor rides on the write
+            rs = torch.rsqrt(torch.linalg.vector_norm(X, dim=-1, dtype=torch.float32).pow(2) / X.shape[-1] + self.eps).contiguous()
+            k = (X @ self.kv["gW_K"]).view(T, self.Hkv, self.d)
+            v = (X @ self.kv["gW_V"]).view(T, self.Hkv, self.d)
+            yb.global_kv_write_scaled(cache, k, v, rs, 0, pos0)
+            return cache
         xn = _rmsnorm(X, self.kv["ln"], self.eps)
         k = (xn @ self.kv["W_K"]).to(self.dtype).view(T, self.Hkv, self.d)
         v = (xn @ self.kv["W_V"]).to(self.dtype).view(T, self.Hkv, self.d)
-        if cache is None:
-            cache = yb.KVCache(1, self.Hkv, self.d, T, self.cache_dtype, self.device)
         yb.global_kv_write(cache, k, v, 0, pos0)
         return cache
 

@@ -91,6 +91,31 @@ def test_global_kv_write_codes_are_exact(yoco, src, N_cap, pos0, n):
         assert np.all(scales[keep].view(np.uint32) == fill.view(np.uint32))
 
 
+@pytest.mark.parametrize("src", ["f32", "bf16"])
+@pytest.mark.parametrize("N_cap,pos0,n", [(300, 60, 200), (100, 37, 63), (640, 128, 512)])
+def test_global_kv_write_scaled_codes_the_scaled_rows(yoco, src, N_cap, pos0, n):
+    """The write that folds the norm of Eq. 2 over an 8-bit cache: every row is multiplied by its factor in float32 and
+    then coded by the same rule, so codes and scales equal the oracle's quantiser on float32(x * factor), bit for bit
+    (block-aligned runs and ragged head / tail rows take different kernels)."""
+    B, Hkv = 2, 3
+    rng = np.random.default_rng(N_cap + pos0 + n)
+    cache = yoco.KVCache(B, Hkv, D, N_cap, torch.int8)
+    cache.mem.fill_(0xAB)
+    k = spread_rows(rng, (n, Hkv, D), src)
+    v = spread_rows(rng, (n, Hkv, D), src)
+    rs = np.exp2(rng.uniform(-3, 3, size=n)).astype(np.float32)
+    yoco.global_kv_write_scaled(cache, dev(k, src), dev(v, src), torch.from_numpy(rs).cuda(), 1, pos0)
+    torch.cuda.synchronize()
+    (kc, ks), (vc, vs) = read_cache(cache)
+    for name, x, codes, scales in (("k", k, kc, ks), ("v", v, vc, vs)):
+        scaled = (x.astype(np.float32) * rs[:, None, None]).astype(np.float32)
+        rc, rsc = oracle.kv_quantise_int8(scaled)
+        assert np.array_equal(codes[1, :, pos0:pos0 + n], rc.transpose(1, 0, 2).astype(np.int16)), name
+        assert np.array_equal(scales[1, :, pos0:pos0 + n].view(np.uint32), rsc.T.copy().view(np.uint32)), name
+        fillc = 0xAB - 256 if name == "k" else 0xAB - 128
+        assert np.all(codes[0] == fillc) and np.all(codes[1, :, :pos0] == fillc) and np.all(codes[1, :, pos0 + n:] == fillc)
+
+
 def test_append_codes_rows_at_device_positions(yoco):
     B, Hkv, N_cap = 5, 2, 200
     rng = np.random.default_rng(11)

@@ -206,6 +206,30 @@ def test_rmsnorm_and_global_kv_against_library():
     assert np.abs(Ki[:, 1, :] - ref[:, 8:16]).max() < 1e-14
 
 
+def test_global_kv_with_the_norm_behind_the_projections_is_the_same_cache():
+    """Eq. 2 in the form the fused write call takes: (1 / rms(x)) * (x (diag(g) W)) equals RMSNorm(x) W to rounding
+    (1e-12 of the largest entry), against the library's rms_norm as well as against oracle.global_kv; the factor is
+    the library norm's own (a row of ones has factor 1 / sqrt(1 + eps)); a wrong eps, a dropped gain or a factor
+    applied per column would each break the equality."""
+    rng = np.random.default_rng(17)
+    X, g = rng.standard_normal((9, 48)) * 3.0, rng.standard_normal(48)
+    WK, WV = rng.standard_normal((48, 24)), rng.standard_normal((48, 24))
+    Kh, Vh = oracle.global_kv(X, g, WK, WV, Hkv=3)
+    Kr, Vr, rs = oracle.global_kv_scaled_form(X, g, WK, WV, Hkv=3)
+    assert Kr.shape == (9, 3, 8) and rs.shape == (9,)
+    big = max(np.abs(Kh).max(), np.abs(Vh).max())
+    assert np.abs(Kr * rs[:, None, None] - Kh).max() <= 1e-12 * big
+    assert np.abs(Vr * rs[:, None, None] - Vh).max() <= 1e-12 * big
+    lib = F.rms_norm(torch.from_numpy(X), (48,), torch.from_numpy(g), eps=1e-6).numpy()
+    assert np.abs((Kr * rs[:, None, None]).reshape(9, 24) - lib @ WK).max() <= 1e-12 * big
+    ones = np.ones((1, 48))
+    assert abs(oracle.global_kv_scaled_form(ones, g, WK, WV, Hkv=3)[2][0] - 1.0 / math.sqrt(1.0 + 1e-6)) < 1e-15
+    # planted mistakes in copies of the scaled form
+    assert np.abs(Kr * (1.0 / np.sqrt((X * X).mean(-1)))[:, None, None] - Kh).max() > 1e-9 * big          # eps dropped
+    assert np.abs((X @ WK).reshape(9, 3, 8) * rs[:, None, None] - Kh).max() > 1e-3 * big                   # gain dropped
+    assert np.abs(Kr * (1.0 / np.sqrt((X * X).sum(-1) + 1e-6))[:, None, None] - Kh).max() > 1e-3 * big     # sum for mean
+
+
 def test_swish_against_library():
     x = np.linspace(-30, 30, 241)
     assert np.abs(oracle.swish(x) - F.silu(torch.from_numpy(x)).numpy()).max() < 1e-13
