@@ -97,6 +97,8 @@ DECODE_CASES = [
     ("bf16", 24, 24, 128, 1024, [1, 700, 1024, 1025, 5000]),    # the self-decoder shape: before, at and after the wrap
     ("bf16", 8, 2, 128, 300, [299, 300, 301, 1000]),            # GQA, window not a multiple of the kernel's chunk
     ("bf16", 4, 4, 128, 1, [1, 9]),                             # window 1: o = v of the new row
+    ("bf16", 12, 2, 128, 700, [699, 700, 701, 3000]),           # 6 query heads per KV head
+    ("bf16", 13, 1, 128, 520, [1, 520, 521, 2000]),             # 13 heads per KV head: two launches, the first stores the row
     ("f32", 4, 4, 64, 128, [5, 128, 129, 512]),                 # the tiny configuration (generic kernels)
     ("f32", 6, 2, 32, 50, [50, 51, 149, 7]),
 ]

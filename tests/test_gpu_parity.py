@@ -258,7 +258,8 @@ def test_cross_attn_prefill_matches_oracle(yoco, dtype, Hq, Hkv, d, N, q_pos0, T
     ("bf16", 6, 2, 128, 3000, 1500, 5),
     ("bf16", 4, 4, 128, 700, 0, 8),          # rows 0..7: the first sees one key
     ("f32", 4, 1, 64, 512, 511, 1),
-    ("bf16", 10, 2, 128, 900, 890, 3),       # G = 5: generic split kernels
+    ("bf16", 10, 2, 128, 900, 890, 3),       # G = 5: the 16-rows-per-step streaming kernel
+    ("bf16", 22, 2, 128, 1900, 1890, 4),     # G = 11: two launches, 6 + 5 heads
 ])
 def test_cross_attn_prefill_few_rows_with_workspace(yoco, dtype, Hq, Hkv, d, N, q_pos0, Tq):
     """With a workspace, calls of up to 8 rows are split over the cache like decode;
@@ -285,7 +286,12 @@ DECODE_CASES = [
     ("bf16", 4, 4, 128, 70000, [69999]),                  # many splits, G = 1
     ("bf16", 8, 2, 128, 3000, [2049, 255]),               # G = 4
     ("bf16", 6, 2, 128, 600, [0, 600]),                   # an empty sequence gives zeros
-    ("bf16", 10, 2, 128, 900, [900]),                     # G = 5 (no streaming fast path)
+    ("bf16", 10, 2, 128, 900, [900]),                     # G = 5: 16 rows per wavefront step
+    ("bf16", 16, 2, 128, 4100, [4100, 33]),               # G = 8, several splits, a ragged tail
+    ("bf16", 7, 1, 128, 2500, [2500, 1, 0]),              # G = 7
+    ("bf16", 9, 1, 128, 1500, [1500, 129]),               # G = 9: two launches, 5 + 4 heads
+    ("bf16", 32, 2, 128, 6000, [5999, 600]),              # G = 16: two launches of 8 heads
+    ("bf16", 34, 2, 128, 600, [600]),                     # G = 17: beyond the streaming kernels (generic split kernels)
     ("bf16", 4, 2, 64, 400, [400, 13]),
     ("bf16", 4, 2, 128, 400, [0, 400, 17]),               # one split: pass 1 stores the output itself; an empty sequence
 ]
