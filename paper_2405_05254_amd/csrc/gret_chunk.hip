@@ -8,16 +8,18 @@
 //   O_[i]    = scale * ((Q K^T * D) V + (Q R_{i-1}) * 2^(G_j)),  D(j,k) = 2^(G_j - G_k), k <= j
 // in four launches:
 //   0  cumulative decays G (one wavefront per chunk)
-//   1  U_i for every chunk in parallel (fp16 MFMA, V scaled while staged)
-//   2  the scan R_i = U_i + a_i R_{i-1}, element-wise over the 128 x 128 state,
-//      leaving R_{i-1} for every chunk as two bf16 planes hi + lo (16
-//      significant bits, fp32's exponent range: no scaling to track)
-//   3  outputs, one workgroup per 128 query rows: the cross-chunk product
-//      R_{i-1}^T Q^T (bf16 MFMA on hi and lo) scaled per row, then the key
-//      tiles of the chunk up to the diagonal as in the sliding-window kernel,
-//      with the decay 2^(G_j - G_k) in place of the softmax; optional GroupNorm
-//      and swish gate (Eq. 7) before the store.
-// States and U are stored transposed ([dv][dk]); this is also the layout of
+//   1  the states, scanned inside a segment: a workgroup walks a run of consecutive chunks of one head with the
+//      running state L in its accumulators (L <- 2^G_last L + U_i after each chunk; fp16 MFMA, V scaled while
+//      staged) and leaves, for every chunk but the first of the run, the state before the chunk *within the
+//      segment* in fp32. U_i itself never reaches memory. The run's total goes out in fp32 as well.
+//   2  the scan across segments (a few states per head, element-wise), leaving the state before each segment
+//   3  outputs, one workgroup per 128 query rows: R_{i-1} = (state before the chunk within its segment) +
+//      2^(decay since the segment's start) * (state before the segment), formed in fp32 while it is staged and
+//      split into two bf16 planes hi + lo (16 significant bits, fp32's exponent range: no scaling to track, and
+//      both feed the bf16 MFMA against the bf16 Q as it stands); the cross-chunk product R_{i-1}^T Q^T (bf16 MFMA on both planes) scaled per
+//      row, then the key tiles of the chunk up to the diagonal as in the sliding-window kernel, with the decay
+//      2^(G_j - G_k) in place of the softmax; optional GroupNorm and swish gate (Eq. 7) before the store.
+// States are stored transposed ([dv][dk]); this is also the layout of
 // the caller's state_in / state_out.
 //
 // Orientation, tiling, LDS swizzles, the fp16 second product (P rounded to fp16,
@@ -43,10 +45,13 @@ constexpr float kLog2e = 1.4426950408889634f;
 struct ChunkArgs {
   GretView a;
   int chunk, nc;       // rows per chunk, chunks per sequence
+  int seg, nseg;       // chunks per segment, segments per sequence
   float* gc;           // [B][H][nc * chunk]   cumulative log2 decay within the chunk, inclusive
-  float* u;            // [B][H][nc][dv][dk]   local states
-  bf16_t* rhi;         // [B][H][nc][dv][dk]   state before the chunk, high part
-  bf16_t* rlo;         //                      and low part
+  float* rw;           // [B][H][nc][dv][dk]   state before the chunk within its segment
+  float* seg_total;    // [B][H][nseg][dv][dk] state a segment adds, started from zero
+  float* seg_init;     // [B][H][nseg][dv][dk] state before the segment
+  float* gpre;         // [B][H][nc]           log2 decay from the start of the chunk's segment to the start of the chunk
+  float* gseg;         // [B][H][nseg]         log2 decay over the whole segment
 };
 
 __device__ __forceinline__ int64_t last_row_of_chunk(const ChunkArgs& g, int c) {
@@ -97,19 +102,22 @@ __device__ __forceinline__ f16x8 tr_frag(lds_char* tile, int base, int blk, int 
   return __builtin_bit_cast(f16x8, vu);
 }
 
-// ---- launch 1: U_i^T = (V * w)^T K over the rows of chunk i. Workgroup = 4 wavefronts, each a 64 x 64 block.
-__global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
+// ---- launch 1: the states of a segment. Workgroup = 4 wavefronts, each a 64 x 64 block of L^T = sum (V * w)^T K;
+// at every chunk boundary inside the segment the block is stored and decayed by the next chunk's 2^G_last.
+__global__ void __launch_bounds__(256, 3) gret_chunk_state_kernel(ChunkArgs g) {
   __shared__ __attribute__((aligned(1024))) char k_t[kTileBytes], v_t[kTileBytes];
   const GretView& a = g.a;
   // heads vary fastest over the grid: workgroups that run together read neighbouring 256-byte segments of the same rows
-  const int h = blockIdx.x, c = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hf = lane >> 5, lq = lane & 31;
-  const int64_t c0 = (int64_t)c * g.chunk;
-  const int64_t last = last_row_of_chunk(g, c);
-  const float* gc = g.gc + (((int64_t)b * a.H + h) * g.nc + c) * g.chunk;
-  const float g_last = gc[last - c0];
+  const int64_t bh = (int64_t)b * a.H + h;
+  const int first = sg * g.seg;                                       // first chunk of the segment
+  const int c_end = first + g.seg < g.nc ? first + g.seg : g.nc;
+  const int64_t r0 = (int64_t)first * g.chunk;
+  const int64_t last = last_row_of_chunk(g, c_end - 1);               // last row of the segment
+  const float* gc = g.gc + bh * g.nc * g.chunk;                       // indexed by the row within the sequence
   const bf16_t* kg = (const bf16_t*)a.k + ((int64_t)b * a.T * a.H + h) * kD;
   const bf16_t* vg = (const bf16_t*)a.v + ((int64_t)b * a.T * a.H + h) * kD;
   const int64_t row_stride = (int64_t)a.H * kD;
@@ -127,21 +135,42 @@ __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int n_tiles = (int)((last - c0) / kBN) + 1;
+  const int tiles_per_chunk = g.chunk / kBN;
+  const int n_tiles = (int)((last - r0) / kBN) + 1;
   u32x4 kr[4], vr[4];
   float w[4];
   auto load_tile = [&](int t0) {
+    const float g_last = gc[last_row_of_chunk(g, first + t0 / tiles_per_chunk)];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int64_t row = c0 + (int64_t)t0 * kBN + srow + 16 * i;
+      const int64_t row = r0 + (int64_t)t0 * kBN + srow + 16 * i;
       const int64_t grow = row <= last ? row : last;                // rows past the end weigh nothing
-      w[i] = row <= last ? __builtin_amdgcn_exp2f(g_last - gc[grow - c0]) : 0.f;
+      w[i] = row <= last ? __builtin_amdgcn_exp2f(g_last - gc[grow]) : 0.f;
       kr[i] = *(const u32x4*)(kg + grow * row_stride + c16 * 8);
       vr[i] = *(const u32x4*)(vg + grow * row_stride + c16 * 8);
     }
   };
   load_tile(0);
+  float gsum = 0.f;                                                  // log2 decay from the segment's start (thread 0 keeps it)
+  if (tid == 0) g.gpre[bh * g.nc + first] = 0.f;
   for (int t0 = 0; t0 < n_tiles; ++t0) {
+    if (t0 > 0 && t0 % tiles_per_chunk == 0) {                       // a chunk of the segment ends here
+      const int c = first + t0 / tiles_per_chunk;                    // the chunk that starts
+      const float decay = __builtin_amdgcn_exp2f(gc[last_row_of_chunk(g, c)]);
+      int lane_off = (mb0 * 32 + hf * 4) * kD + nb0 * 32 + lq;       // kept local: 64 hoisted store addresses cost an occupancy step
+      asm volatile("" : "+v"(lane_off));
+      float* rw = g.rw + (bh * g.nc + c) * kState + lane_off;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            rw[(i * 32 + (r >> 2) * 8 + (r & 3)) * kD + j * 32] = acc[i][j][r];
+            acc[i][j][r] *= decay;
+          }
+      if (tid == 0) g.gpre[bh * g.nc + c] = (gsum += gc[last_row_of_chunk(g, c - 1)]);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int lrow = srow + 16 * i;
@@ -167,7 +196,8 @@ __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
     }
     __syncthreads();
   }
-  float* u = g.u + (((int64_t)b * a.H + h) * g.nc + c) * kState;
+  if (tid == 0) g.gseg[bh * g.nseg + sg] = gsum + gc[last];
+  float* u = g.seg_total + (bh * g.nseg + sg) * kState;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -179,8 +209,8 @@ __global__ void __launch_bounds__(256) gret_chunk_state_kernel(ChunkArgs g) {
       }
 }
 
-// ---- launch 2: scan over the chunks; thread owns 4 consecutive elements of the state. The U_i of a
-// group of chunks are loaded together (independent addresses) before the dependent updates run.
+// ---- launch 2: scan over the segments; thread owns 4 consecutive elements of the state. The totals of a group of
+// segments are loaded together (independent addresses) before the dependent updates run.
 __global__ void __launch_bounds__(256) gret_state_scan_kernel(ChunkArgs g) {
   constexpr int kAhead = 8;
   const GretView& a = g.a;
@@ -190,29 +220,19 @@ __global__ void __launch_bounds__(256) gret_state_scan_kernel(ChunkArgs g) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   f32x4 R = {0.f, 0.f, 0.f, 0.f};
   if (a.state_in) R = *(const f32x4*)(a.state_in + bh * kState + e);
-  const float* gc = g.gc + bh * g.nc * g.chunk;
-  for (int c0 = 0; c0 < g.nc; c0 += kAhead) {
+  for (int s0 = 0; s0 < g.nseg; s0 += kAhead) {
     f32x4 U[kAhead];
     float alpha[kAhead];
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) {
-      const int c = c0 + i < g.nc ? c0 + i : g.nc - 1;
-      U[i] = __builtin_nontemporal_load((const f32x4*)(g.u + (bh * g.nc + c) * kState + e));
-      alpha[i] = __builtin_amdgcn_exp2f(gc[last_row_of_chunk(g, c)]);
+      const int sg = s0 + i < g.nseg ? s0 + i : g.nseg - 1;
+      U[i] = __builtin_nontemporal_load((const f32x4*)(g.seg_total + (bh * g.nseg + sg) * kState + e));
+      alpha[i] = __builtin_amdgcn_exp2f(g.gseg[bh * g.nseg + sg]);
     }
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) {
-      const int c = c0 + i;
-      if (c < g.nc) {
-        const int64_t off = (bh * g.nc + c) * kState + e;
-        u32x2 hi, lo;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-          hi[p] = pack_bf16(R[2 * p], R[2 * p + 1]);
-          lo[p] = pack_bf16(R[2 * p] - __uint_as_float(hi[p] << 16), R[2 * p + 1] - __uint_as_float(hi[p] & 0xffff0000u));
-        }
-        *(u32x2*)(g.rhi + off) = hi;
-        *(u32x2*)(g.rlo + off) = lo;
+      if (s0 + i < g.nseg) {
+        *(f32x4*)(g.seg_init + (bh * g.nseg + s0 + i) * kState + e) = R;
         R = U[i] + alpha[i] * R;
       }
     }
@@ -294,21 +314,46 @@ __global__ void __launch_bounds__(256, 2) gret_chunk_output_kernel(ChunkArgs g) 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_o[mb][r] = 0.f;
 
-  // ---- cross-chunk part: O^T = R_{i-1}^T Q^T, then every query column times scale * 2^(G_q). The two bf16
-  // planes of R^T (128 x 128 each) pass through the four tile buffers, laid out like K tiles.
-  const bool has_past = c > 0 || a.state_in != nullptr;
+  // ---- cross-chunk part: O^T = R_{i-1}^T Q^T, then every query column times scale * 2^(G_q). R_{i-1} is put
+  // together in fp32 from the state before the chunk within its segment and the decayed state before
+  // the segment, and its two bf16 planes (128 x 128 each) pass through the four tile buffers, laid out like K tiles.
+  const int sg = c / g.seg, first = sg * g.seg;
+  const bool has_local = c > first;
+  const bool has_init = sg > 0 || a.state_in != nullptr;
+  const bool has_past = has_local || has_init;
   if (has_past) {
-    const bf16_t* rh = g.rhi + (bh * g.nc + c) * kState;
-    const bf16_t* rl = g.rlo + (bh * g.nc + c) * kState;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const float* rw = g.rw + (bh * g.nc + c) * kState;
+    const float* si = g.seg_init + (bh * g.nseg + sg) * kState;
+    const float fpre = has_init ? __builtin_amdgcn_exp2f(g.gpre[bh * g.nc + c]) : 0.f;
+    // every load of this part, and the first key tile after them, is issued before anything waits
+    f32x4 wl[8][2], wi[8][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = srow + 16 * i;                              // rows 0..63 of a half plane
-      *(u32x4*)(k_a + kst_off + i * 4096) = *(const u32x4*)(rh + row * kD + c16 * 8);
-      *(u32x4*)(k_b + kst_off + i * 4096) = *(const u32x4*)(rh + (64 + row) * kD + c16 * 8);
-      *(u32x4*)(v_a + kst_off + i * 4096) = *(const u32x4*)(rl + row * kD + c16 * 8);
-      *(u32x4*)(v_b + kst_off + i * 4096) = *(const u32x4*)(rl + (64 + row) * kD + c16 * 8);
+    for (int i = 0; i < 8; ++i) {                                   // rows srow + 16 i of both planes
+      const int off = (srow + 16 * i) * kD + c16 * 8;
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        wl[i][p] = has_local ? *(const f32x4*)(rw + off + 4 * p) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        wi[i][p] = has_init ? *(const f32x4*)(si + off + 4 * p) : (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
     }
-    load_tile(jt_lo);                                             // in flight during the product
+    load_tile(jt_lo);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      u32x4 hi, lo;
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const float x0 = fmaf(fpre, wi[i][p][2 * e], wl[i][p][2 * e]);
+          const float x1 = fmaf(fpre, wi[i][p][2 * e + 1], wl[i][p][2 * e + 1]);
+          const unsigned hw = pack_bf16(x0, x1);
+          hi[2 * p + e] = hw;
+          lo[2 * p + e] = pack_bf16(x0 - __uint_as_float(hw << 16), x1 - __uint_as_float(hw & 0xffff0000u));
+        }
+      *(u32x4*)((i >= 4 ? k_b : k_a) + kst_off + (i & 3) * 4096) = hi;
+      *(u32x4*)((i >= 4 ? v_b : v_a) + kst_off + (i & 3) * 4096) = lo;
+    }
     __syncthreads();
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
@@ -458,10 +503,20 @@ bool gret_chunk_supported(int B, int64_t T, int H, int dk, int dv, int chunk, in
   return B <= 65535;
 }
 
+// Chunks per segment: long enough that the states written per chunk are the only state traffic, short enough that
+// the state launch still fills the chip at its occupancy (3 workgroups on each of 256 CUs) when the shape allows it.
+int gret_segment_chunks(int B, int H, int nc) {
+  int64_t s = (int64_t)nc * B * H / 768;
+  if (s < 1) s = 1;
+  if (s > 16) s = 16;
+  return (int)s;
+}
+
 size_t gret_chunk_workspace(int B, int64_t T, int H, int chunk) {
   const size_t nc = (size_t)((T + chunk - 1) / chunk), bh = (size_t)B * H;
+  const size_t seg = (size_t)gret_segment_chunks(B, H, (int)nc), nseg = (nc + seg - 1) / seg;
   return align256(bh * nc * chunk * sizeof(float)) + align256(bh * nc * kState * sizeof(float)) +
-         2 * align256(bh * nc * kState * sizeof(bf16_t));
+         2 * align256(bh * nseg * kState * sizeof(float)) + align256(bh * nc * sizeof(float)) + align256(bh * nseg * sizeof(float));
 }
 
 hipError_t launch_gret_chunk(const GretView& a, int chunk, void* workspace, hipStream_t s) {
@@ -469,17 +524,23 @@ hipError_t launch_gret_chunk(const GretView& a, int chunk, void* workspace, hipS
   g.a = a;
   g.chunk = chunk;
   g.nc = (int)((a.T + chunk - 1) / chunk);
+  g.seg = gret_segment_chunks(a.B, a.H, g.nc);
+  g.nseg = (g.nc + g.seg - 1) / g.seg;
   const size_t bh = (size_t)a.B * a.H;
   char* p = (char*)workspace;
   g.gc = (float*)p;
   p += align256(bh * g.nc * chunk * sizeof(float));
-  g.u = (float*)p;
+  g.rw = (float*)p;
   p += align256(bh * g.nc * kState * sizeof(float));
-  g.rhi = (bf16_t*)p;
-  p += align256(bh * g.nc * kState * sizeof(bf16_t));
-  g.rlo = (bf16_t*)p;
+  g.seg_total = (float*)p;
+  p += align256(bh * g.nseg * kState * sizeof(float));
+  g.seg_init = (float*)p;
+  p += align256(bh * g.nseg * kState * sizeof(float));
+  g.gpre = (float*)p;
+  p += align256(bh * g.nc * sizeof(float));
+  g.gseg = (float*)p;
   hipLaunchKernelGGL(gret_cumdecay_kernel, dim3(g.nc, a.H, a.B), dim3(64), 0, s, g);
-  hipLaunchKernelGGL(gret_chunk_state_kernel, dim3(a.H, g.nc, a.B), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(gret_chunk_state_kernel, dim3(a.H, g.nseg, a.B), dim3(256), 0, s, g);
   hipLaunchKernelGGL(gret_state_scan_kernel, dim3(kState / 1024, a.H, a.B), dim3(256), 0, s, g);
   hipLaunchKernelGGL(gret_chunk_output_kernel, dim3(a.H, (unsigned)((a.T + kBM - 1) / kBM), a.B), dim3(256), 0, s, g);
   return hipGetLastError();

@@ -156,8 +156,14 @@ def test_gated_retention_calls_validate_before_launching():
     n = C.c_size_t()
     # workspace sizing: only bf16, dk = dv = 128, chunk a multiple of 128 has a chunkwise path
     assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 256, yoco.BF16, C.byref(n)) == 0
-    nc = 4
-    assert n.value == 4 * (nc * 256 * 4 + nc * 128 * 128 * 4 + 2 * nc * 128 * 128 * 2)
+    # cumulative decays, one fp32 state per chunk, two per segment (here every chunk is its own segment), and two
+    # small decay tables, each rounded up to 256 bytes
+    bh, nc, nseg, state = 4, 4, 4, 128 * 128 * 4
+    up = lambda x: (x + 255) // 256 * 256
+    assert n.value == up(bh * nc * 256 * 4) + up(bh * nc * state) + 2 * up(bh * nseg * state) + up(bh * nc * 4) + up(bh * nseg * 4)
+    assert L.yoco_gret_prefill_workspace(1, 32768, 24, 128, 128, 256, yoco.BF16, C.byref(n)) == 0
+    bh, nc, nseg = 24, 128, 32                      # long inputs: segments of 4 chunks
+    assert n.value == up(bh * nc * 256 * 4) + up(bh * nc * state) + 2 * up(bh * nseg * state) + up(bh * nc * 4) + up(bh * nseg * 4)
     for args in ((1, 1000, 4, 64, 128, 256, yoco.BF16), (1, 1000, 4, 128, 128, 256, yoco.F32), (1, 1000, 4, 128, 128, 200, yoco.BF16)):
         assert L.yoco_gret_prefill_workspace(*args, C.byref(n)) == 0 and n.value == 0
     assert L.yoco_gret_prefill_workspace(1, 1000, 4, 128, 128, 0, yoco.BF16, C.byref(n)) == -1
