@@ -49,6 +49,29 @@ def swa_flops(T, H, d, C):
     return 4.0 * d * pairs * H
 
 
+def graph_ms(step, reps):
+    """Average duration of `step` (a run of library launches on the current stream) replayed from a HIP graph:
+    the launch-bound decode loops as a serving loop would issue them, without the per-call host time of Python."""
+    import torch
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    times = []
+    for rep in range(2 + reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            times.append(e0.elapsed_time(e1))
+    return sum(times) / len(times)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -259,8 +282,15 @@ def main():
         ms = sum(times) / len(times)
         ring_bytes = 2.0 * B * Cw * Hs * d * 2
         gbs = layers * ring_bytes / (ms * 1e-3) / 1e9
+
+        def swa_step():
+            for i in range(layers):
+                yoco.swa_decode(rings[i], qs[i], ln, scale, w, out=od, k_new=k_new, v_new=k_new)
+        gms = graph_ms(swa_step, len(times))
         decode["swa_decode_b16_w1024"] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4),
                                               GBps=round(gbs, 1), frac_of_hbm_peak=round(gbs / HBM_PEAK_GBS, 4),
+                                              hip_graph_ms_per_13_layers=round(gms, 4),
+                                              hip_graph_frac_of_hbm_peak=round(layers * ring_bytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                               splits=splits, ring_bytes_per_layer=int(ring_bytes))
         del rings, qs, w
         torch.cuda.empty_cache()
@@ -307,9 +337,16 @@ def main():
                 times.append(e0.elapsed_time(e1))
         ms = sum(times) / len(times)
         sbytes = 2.0 * Bd * H * d * d * 4                                  # the state read and written once
+
+        def gret_step():
+            for i in range(layers):
+                yoco.gret_decode(dq, dq, dq, dlg, states[i], scale, out=do)
+        gms = graph_ms(gret_step, len(times))
         gret["decode_b16"] = dict(ms_per_13_layers=round(ms, 4), ms_per_layer=round(ms / layers, 4),
                                   GBps=round(layers * sbytes / (ms * 1e-3) / 1e9, 1),
                                   frac_of_hbm_peak=round(layers * sbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  hip_graph_ms_per_13_layers=round(gms, 4),
+                                  hip_graph_frac_of_hbm_peak=round(layers * sbytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                   state_bytes_per_layer=int(sbytes / 2))
         del states
         torch.cuda.empty_cache()

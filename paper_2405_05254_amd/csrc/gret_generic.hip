@@ -125,6 +125,79 @@ __global__ void __launch_bounds__(256) gret_recurrent_kernel(GretView a) {
 
 }
 
+// ---- the decode step (T = 1) at dk = dv = 128, state updated in place: same thread -> state mapping as above, but
+// written for the memory system. The small operands are requested before the state, so that the first rows can be
+// worked on as soon as they land (loads come back in issue order); the state moves in four quarters of four rows per
+// thread with two quarters in flight, and a quarter is stored as soon as it is updated, so the launch reads and writes
+// at the same time instead of in two phases; the 16 row sums of a thread are reduced together (at every exchange a
+// lane keeps half of its rows: 16 exchanges instead of 80), after which lane pair kk / 2 of a half wavefront holds
+// row rr + 8 (kk / 2).
+template <typename T>
+__global__ void __launch_bounds__(256) gret_decode_kernel(GretView a) {
+  constexpr int kDim = 128;
+  __shared__ float red[4];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int kk = threadIdx.x & 31, rr = threadIdx.x >> 5;
+  const int ek = kk * 4;
+  const size_t bh = (size_t)b * a.H + h;
+  const T* q = (const T*)a.q + bh * kDim;
+  const T* k = (const T*)a.k + bh * kDim;
+  const T* v = (const T*)a.v + bh * kDim;
+  float* st = a.state_out + bh * kDim * kDim + (size_t)rr * kDim + ek;    // row rr + 8 r is 8 r rows further
+
+  const float gamma = __expf(a.log_gamma[bh]);
+  const f32x4 kf = load4<T>(k + ek), qf = load4<T>(q + ek);
+  float vv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) vv[r] = Elem<T>::load(v + rr + 8 * r);
+
+  f32x4 S[16];
+  auto load_quarter = [&](int qt) {
+#pragma unroll
+    for (int r = 4 * qt; r < 4 * qt + 4; ++r) S[r] = __builtin_nontemporal_load((const f32x4*)(st + (size_t)r * 8 * kDim));
+  };
+  float part[16];
+  load_quarter(0);
+  load_quarter(1);
+#pragma unroll
+  for (int qt = 0; qt < 4; ++qt) {
+    if (qt + 2 < 4) load_quarter(qt + 2);
+#pragma unroll
+    for (int r = 4 * qt; r < 4 * qt + 4; ++r) {
+      S[r] = gamma * S[r] + kf * vv[r];
+      __builtin_nontemporal_store(S[r], (f32x4*)(st + (size_t)r * 8 * kDim));
+      part[r] = qf[0] * S[r][0] + qf[1] * S[r][1] + qf[2] * S[r][2] + qf[3] * S[r][3];
+    }
+  }
+  // reduce-scatter over the 32 lanes of the half wavefront
+#pragma unroll
+  for (int w = 8, o = 16; w >= 1; w >>= 1, o >>= 1) {       // w rows stay per lane after the exchange with lane ^ o
+    const bool upper = (kk & o) != 0;
+#pragma unroll
+    for (int i = 0; i < w; ++i) {
+      const float send = upper ? part[i] : part[i + w];
+      const float keep = upper ? part[i + w] : part[i];
+      part[i] = keep + __shfl_xor(send, o);
+    }
+  }
+  float out = a.scale * (part[0] + __shfl_xor(part[0], 1));
+  const int ev = rr + 8 * (kk >> 1);                         // the row this lane pair holds: bit o of kk chose its half at exchange o
+  if (a.group_norm) {
+    const float inv_dv = 1.f / (float)kDim;
+    const float mean = block_sum((kk & 1) ? 0.f : out, red) * inv_dv;
+    const float dlt = out - mean;
+    const float var = block_sum((kk & 1) ? 0.f : dlt * dlt, red) * inv_dv;
+    out = dlt * rsqrtf(var + a.eps);
+  }
+  if (!(kk & 1)) {
+    if (a.gate) {                                            // swish gate of Eq. 7: y * g * sigmoid(g)
+      const float gv = Elem<T>::load((const T*)a.gate + bh * kDim + ev);
+      out *= gv / (1.f + __expf(-gv));
+    }
+    Elem<T>::store((T*)a.o + bh * kDim + ev, out);
+  }
+}
+
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
 }
@@ -146,6 +219,13 @@ bool gret_recurrent_supported(const GretView& a) {
 
 hipError_t launch_gret_recurrent(const GretView& a, int dtype, hipStream_t s) {
   dim3 grid(a.H, a.B), block(256);
+  if (a.T == 1 && a.dk == 128 && a.dv == 128 && a.state_in && a.state_in == a.state_out) {   // the decode step
+    if (dtype == YOCO_F32)
+      hipLaunchKernelGGL(gret_decode_kernel<float>, grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL(gret_decode_kernel<bf16_t>, grid, block, 0, s, a);
+    return hipGetLastError();
+  }
   if (dtype == YOCO_F32)
     hipLaunchKernelGGL(gret_recurrent_kernel<float>, grid, block, 0, s, a);
   else
