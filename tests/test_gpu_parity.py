@@ -320,6 +320,54 @@ def test_cross_attn_decode_matches_oracle(yoco, dtype, Hq, Hkv, d, N_cap, lens):
     assert torch.equal(o, o2)
 
 
+@pytest.mark.parametrize("Hq,Hkv,std,N,lens", [
+    (6, 2, 4.0, 3000, [3000, 2049, 31]),      # scores of +-100: a few rows carry all the weight, the running maximum keeps moving
+    (16, 2, 4.0, 2100, [2100, 1]),            # the same with 8 heads per KV head
+    (6, 2, 0.05, 1500, [1500, 700]),          # nearly uniform weights over the whole cache
+    (32, 2, 1.0, 777, [777, 776]),            # 16 heads per KV head, lengths one apart around a step boundary
+])
+def test_cross_attn_decode_peaky_and_flat_weights(yoco, Hq, Hkv, std, N, lens):
+    """The decode step at the two ends of the softmax: large scores (the output rescale runs often and P's bf16
+    high part + remainder must carry weights that differ by many orders of magnitude) and nearly equal ones."""
+    d, B = 128, len(lens)
+    scale = 1.0 / math.sqrt(d)
+    cache, ks, vs = make_cache(yoco, B, Hkv, d, N, "bf16", 150, [N] * B, std=std)
+    qn = ys.normal(np.random.default_rng(151), (B, Hq, d), std, "bf16")
+    nbytes, splits = yoco.cross_attn_decode_workspace(cache, Hq)
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    o = yoco.cross_attn_decode(cache, dev(qn, "bf16"), torch.tensor(lens, dtype=torch.int64, device="cuda"), scale, ws)
+    torch.cuda.synchronize()
+    on = host(o)
+    for b, n in enumerate(lens):
+        ref = oracle.cross_attn(qn[b:b + 1], ks[b], vs[b], n - 1, scale)[0]
+        check_scaled(on[b], ref, "decode std=%g G=%d b=%d len=%d splits=%d" % (std, Hq // Hkv, b, n, splits))
+
+
+def test_cross_attn_decode_full_size_eight_heads_per_kv_head(yoco):
+    """A 65B-like head layout (64 query heads over 8 KV heads, section 4.4's GQA setting) on 4 x 32768 rows:
+    four (sequence, KV head) pairs, all 8 heads of each, against the oracle on the same bits."""
+    B, N, Hq, Hkv, d = 4, 32768, 64, 8, 128
+    scale = 1.0 / math.sqrt(d)
+    cache = yoco.KVCache(B, Hkv, d, N, torch.bfloat16)
+    Kp, Vp = cache.planes()
+    Kp.copy_(ys.device_normal(Kp.shape, 700, 1.0, torch.bfloat16, "cuda"))
+    Vp.copy_(ys.device_normal(Vp.shape, 701, 1.0, torch.bfloat16, "cuda"))
+    q = ys.device_normal((B, Hq, d), 702, 1.0, torch.bfloat16, "cuda")
+    lens = torch.tensor([N, N - 1, 20000, N], dtype=torch.int64, device="cuda")
+    nbytes, splits = yoco.cross_attn_decode_workspace(cache, Hq)
+    o = yoco.cross_attn_decode(cache, q, lens, scale, torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    on, qn, G = host(o), host(q), Hq // Hkv
+    got, ref = [], []
+    for b, g in ((0, 0), (1, 3), (2, 5), (3, 7)):
+        n = int(lens[b])
+        Kh, Vh = host(Kp[b, g])[:, None, :], host(Vp[b, g])[:, None, :]
+        for h in range(g * G, (g + 1) * G):
+            got.append(on[b, h])
+            ref.append(oracle.cross_attn_row(qn[b:b + 1, h:h + 1], Kh, Vh, 0, 0, n - 1, scale))
+    check(np.array(got), np.array(ref), "bf16", "decode 4 x 32K, 64:8 heads, splits=%d" % splits)
+
+
 @pytest.mark.parametrize("name", ["decode_b16_32k", "decode_b1_512k"])
 def test_cross_attn_decode_full_size(yoco, name):
     """The benchmark's decode launches (16 x 32K and 1 x 512K caches, 24:8 heads),
