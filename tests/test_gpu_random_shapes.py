@@ -42,7 +42,7 @@ def check(got, ref, dtype, what, relative=False):
 
 def draw_heads(rng):
     Hkv = int(rng.integers(1, 4))
-    return Hkv * int(rng.choice([1, 1, 2, 3, 4, 5])), Hkv
+    return Hkv * int(rng.choice([1, 1, 2, 3, 4, 5, 7, 8, 12, 16])), Hkv
 
 
 def draw_len(rng, hi=420):
