@@ -235,7 +235,8 @@ __global__ void __launch_bounds__(256) decode_bf16_kernel(yoco_kv_cache c, const
 }
 
 
-// ---- 5..16 query heads per KV head: both products on the matrix cores, so the stream stays HBM-bound.
+// ---- 1..16 query heads per KV head: both products on the matrix cores, so the stream stays HBM-bound whatever
+// the group size (the heads are the 16 columns of the MFMA; unused columns carry zeros).
 // Wavefront step = 32 rows. Scores: S[key, head] = K[key, :] . Q[head, :] as two 16-key tiles of four
 // 16x16x32 products, K fragments loaded from the row-major plane as they are (lane = (key, 8-dim group)).
 // Output: O^T[dim, head] += V^T[dim, key] P^T[key, head]; the V fragment (8 keys of one dim per lane) comes
