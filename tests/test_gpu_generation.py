@@ -98,7 +98,9 @@ DECODE_CASES = [
     ("bf16", 8, 2, 128, 300, [299, 300, 301, 1000]),            # GQA, window not a multiple of the kernel's chunk
     ("bf16", 4, 4, 128, 1, [1, 9]),                             # window 1: o = v of the new row
     ("bf16", 12, 2, 128, 700, [699, 700, 701, 3000]),           # 6 query heads per KV head
-    ("bf16", 13, 1, 128, 520, [1, 520, 521, 2000]),             # 13 heads per KV head: two launches, the first stores the row
+    ("bf16", 13, 1, 128, 520, [1, 520, 521, 2000]),             # 13 heads per KV head (the matrix-core kernel stores the row)
+    # 384 (sequence, head) units on 256 CUs: two splits each, the split that owns the slot stores the row
+    ("bf16", 24, 24, 128, 2048, [1, 2047, 2048, 2049, 2500, 1025, 1024, 3000, 5, 4096, 4097, 1023, 1026, 2, 3071, 3073]),
     ("f32", 4, 4, 64, 128, [5, 128, 129, 512]),                 # the tiny configuration (generic kernels)
     ("f32", 6, 2, 32, 50, [50, 51, 149, 7]),
 ]
