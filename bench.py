@@ -227,6 +227,11 @@ def main():
                  "operands (every MFMA's A operand a fresh LDS fragment; then with the softmax work of 32 scores per lane and 32 "
                  "MFMAs interleaved): no staging, masks, barriers or tile walk, i.e. what the prefill kernel could reach at best; "
                  "and a 2 GiB streaming read with 128-bit nontemporal loads (best of 1, 2 and 4 workgroups per CU)")
+        # the MFMA-only loop keeps the matrix pipe full (32 clocks per v_mfma_f32_32x32x16, measured), so its rate is a
+        # reading of the clock the chip holds under that load: 2516.6 TFLOP/s is the pipe at 2.4 GHz
+        ceilings["clock_GHz_in_the_mfma_loop"] = dict(
+            random_operands=round(2.4 * ceilings["mfma_bf16_TFLOPs_random_operands"] / MFMA_BF16_PEAK_TFLOPS, 3),
+            zero_operands=round(2.4 * ceilings["mfma_bf16_TFLOPs_zero_operands"] / MFMA_BF16_PEAK_TFLOPS, 3))
         del big
 
     # ---- the decode workloads of the metric: 13 cross-decoder layers over one shared cache
